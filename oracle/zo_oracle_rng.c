@@ -1,0 +1,247 @@
+/*
+ * CPU oracle, part 1: the random direction z and the in-place perturbation.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+ * HIP library is checked against.  Nothing in the product path may call it,
+ * and it shares no code, header, table or constant generator with the HIP
+ * sources: every constant below is typed in here by hand from the written
+ * specification of the generator.
+ *
+ * What it follows (DistZO2, arXiv 2507.03211):
+ *   - Preliminaries, Eq. 1-2: z ~ N(0, I), theta <- theta -/+ (scalar) * z.
+ *   - Appendix A, Alg. 1 (MeZO): PerturbParameters / UpdateParameters visit
+ *     every tensor, draw z_i of that tensor's shape and add (scalar * z_i);
+ *     the generator is reset to the step's seed before each pass so that all
+ *     passes of one step see the same z.
+ *   - PertP workflow, Step 1: a shared seed must give the same z everywhere.
+ * The paper names no generator.  The reading taken here: z is a pure function
+ * of (seed, tensor id, element index) through the counter-based Philox4x32-10
+ * generator (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as
+ * 1, 2, 3", SC'11) followed by a pair-wise Box-Muller transform whose fp32
+ * arithmetic is fixed operation by operation, so that "reset the seed" becomes
+ * "use the same counters" and the bits can be reproduced on any IEEE-754
+ * machine.
+ *
+ * Precision: z is DEFINED in fp32 (this is part of the method's specification,
+ * not an approximation of something else); the perturbation is one fp32 fused
+ * multiply-add followed by round-to-nearest-even into the storage type.
+ *
+ * Pins (tests/test_oracle_rng.py): published Philox known-answer vectors, a
+ * second implementation with Python integers, the closed form
+ * sqrt(-2 ln u) (cos, sin)(angle) in fp64, moments and a KS test, numpy's
+ * float16 cast for the half rounding, chunking invariance.
+ *
+ * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+/* ---------------------------------------------------------------- Philox */
+
+/* One Philox4x32 block, 10 rounds.  The round, as the SC'11 paper defines it:
+ *   (c0,c1,c2,c3) <- (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1, lo(M0*c0))
+ * with the key bumped by the Weyl constants between rounds. */
+void zo_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) { k0 += W0; k1 += W1; }
+        uint64_t p0 = M0 * (uint64_t)c0;
+        uint64_t p1 = M1 * (uint64_t)c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Counter layout: key = (seed low word, seed high word);
+ * counter = (j low word, j high word, tensor id, stream tag), j = element/4.
+ * Stream tag 0 is the perturbation direction z. */
+static void block_for(uint64_t seed, uint32_t tensor_id, uint32_t stream_tag, uint64_t j, uint32_t out[4])
+{
+    uint32_t ctr[4] = { (uint32_t)j, (uint32_t)(j >> 32), tensor_id, stream_tag };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    zo_oracle_philox4x32_10(ctr, key, out);
+}
+
+/* ------------------------------------------------------ normal transform */
+
+static float u32_as_f32(uint32_t x) { float f; memcpy(&f, &x, 4); return f; }
+static uint32_t f32_as_u32(float f) { uint32_t x; memcpy(&x, &f, 4); return x; }
+
+/* Two standard normals from two 32-bit words (pair-wise Box-Muller).
+ *   u     = (2*(ra>>9)+1) * 2^-24               in (0,1), exact in fp32
+ *   q     = rb >> 30                            quadrant
+ *   k     = (rb >> 6) & 0xFFFFFF                fraction of a quarter turn, f = k*2^-24
+ *   rho   = sqrt(-2 ln u),  (z0, z1) = rho * (cos, sin)((q + f) * pi/2)
+ * Every floating-point step is a single IEEE fp32 operation (mul, add, fma,
+ * sqrt); fmaf() is the fused one. */
+void zo_oracle_normal_pair(uint32_t ra, uint32_t rb, float *z0, float *z1)
+{
+    /* radius: t = -2 ln u */
+    float u = (float)(2u * (ra >> 9) + 1u) * 0x1p-24f;
+    uint32_t ix = f32_as_u32(u) - 0x3f3504f3u;          /* bits of sqrt(1/2) */
+    int32_t e = (int32_t)ix >> 23;                      /* u = m * 2^e, m in [sqrt(1/2), sqrt 2) */
+    float m = u32_as_f32((ix & 0x007fffffu) + 0x3f3504f3u);
+    float r = m - 1.0f;
+    /* ln(1+r) = r - r^2/2 + r^3 Q(r) */
+    float Q = -0x1.38b2a8p-4f;
+    Q = fmaf(Q, r, 0x1.055ad8p-3f);
+    Q = fmaf(Q, r, -0x1.0d8586p-3f);
+    Q = fmaf(Q, r, 0x1.22da36p-3f);
+    Q = fmaf(Q, r, -0x1.547240p-3f);
+    Q = fmaf(Q, r, 0x1.99a008p-3f);
+    Q = fmaf(Q, r, -0x1.000228p-2f);
+    Q = fmaf(Q, r, 0x1.555554p-2f);
+    float r2 = r * r;
+    float r3 = r2 * r;
+    float lnm = fmaf(r3, Q, fmaf(-0.5f, r2, r));
+    float lnu = fmaf((float)e, 0x1.62e430p-1f, lnm);    /* + e * ln 2 */
+    float t = -2.0f * lnu;
+    float rho = sqrtf(t);                                /* correctly rounded */
+
+    /* angle: fold the quarter turn at its middle so the polynomials only see [0, 1/2] */
+    uint32_t k = (rb >> 6) & 0xFFFFFFu;
+    int fold = k >= 0x800000u;
+    uint32_t kf = fold ? 0x1000000u - k : k;
+    float f = (float)kf * 0x1p-24f;                      /* exact */
+    float w = f * f;
+    float S = -0x1.2d9302p-8f;                           /* sin(pi f/2) = f * S(w) */
+    S = fmaf(S, w, 0x1.465e92p-4f);
+    S = fmaf(S, w, -0x1.4abbbap-1f);
+    S = fmaf(S, w, 0x1.921fb6p+0f);
+    float sn = f * S;
+    float Cc = 0x1.d9f7b8p-11f;                          /* cos(pi f/2) = 1 + w * C(w) */
+    Cc = fmaf(Cc, w, -0x1.55c664p-6f);
+    Cc = fmaf(Cc, w, 0x1.03c1dep-2f);
+    Cc = fmaf(Cc, w, -0x1.3bd3ccp+0f);
+    float cs = fmaf(w, Cc, 1.0f);
+    if (fold) { float tmp = cs; cs = sn; sn = tmp; }     /* cos(x) = sin(pi/2 - x) */
+    /* rotate by q quarter turns */
+    uint32_t q = rb >> 30;
+    float c, s;
+    switch (q) {
+    case 0: c = cs;  s = sn;  break;
+    case 1: c = -sn; s = cs;  break;
+    case 2: c = -cs; s = -sn; break;
+    default: c = sn; s = -cs; break;
+    }
+    *z0 = rho * c;
+    *z1 = rho * s;
+}
+
+/* z for the elements [first, first+n) of one tensor.  Words (r0,r1) of block j
+ * give elements 4j and 4j+1, words (r2,r3) give 4j+2 and 4j+3. */
+void zo_oracle_z(uint64_t seed, uint32_t tensor_id, uint32_t stream_tag, uint64_t first, uint64_t n, float *out)
+{
+    if (n == 0) return;
+    #pragma omp parallel for schedule(static)
+    for (int64_t jj = (int64_t)(first / 4); jj <= (int64_t)((first + n - 1) / 4); ++jj) {
+        uint32_t w[4];
+        float z[4];
+        block_for(seed, tensor_id, stream_tag, (uint64_t)jj, w);
+        zo_oracle_normal_pair(w[0], w[1], &z[0], &z[1]);
+        zo_oracle_normal_pair(w[2], w[3], &z[2], &z[3]);
+        for (int l = 0; l < 4; ++l) {
+            uint64_t i = 4u * (uint64_t)jj + (uint64_t)l;
+            if (i >= first && i < first + n) out[i - first] = z[l];
+        }
+    }
+}
+
+/* --------------------------------------------------- storage-type rounding */
+
+/* dtype codes of the boundary: 0 fp32, 1 bf16, 2 fp16. */
+uint16_t zo_oracle_f32_to_bf16(float f)
+{
+    uint32_t x = f32_as_u32(f);
+    if ((x & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x >> 16) | 0x0040u); /* quiet NaN */
+    uint32_t lsb = (x >> 16) & 1u;
+    x += 0x7fffu + lsb;                                   /* round to nearest, ties to even */
+    return (uint16_t)(x >> 16);
+}
+float zo_oracle_bf16_to_f32(uint16_t h) { return u32_as_f32((uint32_t)h << 16); }
+
+uint16_t zo_oracle_f32_to_f16(float f)
+{
+    uint32_t x = f32_as_u32(f);
+    uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+    uint32_t a = x & 0x7fffffffu;
+    if (a > 0x7f800000u) return (uint16_t)(sign | 0x7e00u);           /* NaN */
+    if (a >= 0x47800000u) {                                            /* >= 65536: Inf (or Inf in) */
+        return (uint16_t)(sign | 0x7c00u);
+    }
+    if (a >= 0x38800000u) {                                            /* normal half range: >= 2^-14 */
+        uint32_t mant = a & 0x007fffffu;
+        uint32_t exp = (a >> 23) - 112u;                               /* rebias 127 -> 15 */
+        uint32_t h = (exp << 10) | (mant >> 13);
+        uint32_t rem = mant & 0x1fffu;
+        if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) h += 1u;    /* may carry into exponent / Inf: correct */
+        return (uint16_t)(sign | h);
+    }
+    if (a < 0x33000000u) return sign;                                  /* < 2^-25: rounds to zero */
+    /* subnormal half: value = mant24 * 2^(e-150), result unit 2^-24 */
+    uint32_t mant = (a & 0x007fffffu) | 0x00800000u;
+    uint32_t shift = 126u - (a >> 23);                                 /* 14..24 */
+    uint32_t h = mant >> shift;
+    uint32_t rem = mant & ((1u << shift) - 1u);
+    uint32_t half = 1u << (shift - 1u);
+    if (rem > half || (rem == half && (h & 1u))) h += 1u;
+    return (uint16_t)(sign | h);
+}
+float zo_oracle_f16_to_f32(uint16_t h)
+{
+    uint32_t sign = ((uint32_t)h & 0x8000u) << 16;
+    uint32_t exp = (h >> 10) & 0x1fu, mant = h & 0x3ffu;
+    if (exp == 0x1fu) return u32_as_f32(sign | 0x7f800000u | (mant << 13));
+    if (exp != 0) return u32_as_f32(sign | ((exp + 112u) << 23) | (mant << 13));
+    float v = (float)mant * 0x1p-24f;                                  /* subnormal or zero, exact */
+    return sign ? -v : v;
+}
+
+static float load_as_f32(const void *p, int dtype, uint64_t i)
+{
+    if (dtype == 0) return ((const float *)p)[i];
+    if (dtype == 1) return zo_oracle_bf16_to_f32(((const uint16_t *)p)[i]);
+    return zo_oracle_f16_to_f32(((const uint16_t *)p)[i]);
+}
+static void store_from_f32(void *p, int dtype, uint64_t i, float v)
+{
+    if (dtype == 0) ((float *)p)[i] = v;
+    else if (dtype == 1) ((uint16_t *)p)[i] = zo_oracle_f32_to_bf16(v);
+    else ((uint16_t *)p)[i] = zo_oracle_f32_to_f16(v);
+}
+
+/* ---------------------------------------------------- perturb and update */
+
+/* Alg. 1, PerturbParameters / UpdateParameters for one tensor (or a slice of
+ * it): dst[i] <- rn(fma(scale, z_i, src[i])) for i in [first, first+n), where
+ * the pointers address element `first`.  dst may equal src (in place).
+ * scale = +eps, -2 eps, +eps for the three perturbations and -(lr*g) for the
+ * update of Eq. 2. */
+void zo_oracle_axpy_z(const void *src, void *dst, int dtype, uint64_t seed, uint32_t tensor_id,
+                      uint64_t first, uint64_t n, float scale)
+{
+    if (n == 0) return;
+    #pragma omp parallel for schedule(static)
+    for (int64_t jj = (int64_t)(first / 4); jj <= (int64_t)((first + n - 1) / 4); ++jj) {
+        uint32_t w[4];
+        float z[4];
+        block_for(seed, tensor_id, 0u, (uint64_t)jj, w);
+        zo_oracle_normal_pair(w[0], w[1], &z[0], &z[1]);
+        zo_oracle_normal_pair(w[2], w[3], &z[2], &z[3]);
+        for (int l = 0; l < 4; ++l) {
+            uint64_t i = 4u * (uint64_t)jj + (uint64_t)l;
+            if (i < first || i >= first + n) continue;
+            float th = load_as_f32(src, dtype, i - first);
+            store_from_f32(dst, dtype, i - first, fmaf(scale, z[l], th));
+        }
+    }
+}

@@ -1,0 +1,213 @@
+"""Pins for the oracle's random direction z and in-place perturbation
+(oracle/zo_oracle_rng.c): things fixed by the published generator, by the
+closed form of the Box-Muller transform, by library casts and by exact
+rational arithmetic -- never by the oracle's own output."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle import philox_ints
+from oracle import zo_oracle as zo
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _kat():
+    rows = []
+    for line in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        w = [int(x, 16) for x in line.split()]
+        rows.append((w[0:4], w[4:6], tuple(w[6:10])))
+    return rows
+
+
+def test_philox_known_answers_c_and_python():
+    rows = _kat()
+    assert len(rows) == 3
+    for ctr, key, want in rows:
+        assert zo.philox(ctr, key) == want
+        assert philox_ints.philox4x32(ctr, key) == want
+
+
+def test_philox_two_implementations_agree_on_random_counters():
+    rng = np.random.default_rng(7)
+    for _ in range(300):
+        ctr = [int(x) for x in rng.integers(0, 2**32, 4)]
+        key = [int(x) for x in rng.integers(0, 2**32, 2)]
+        assert zo.philox(ctr, key) == philox_ints.philox4x32(ctr, key)
+
+
+def test_philox_fewer_rounds_differ():
+    # a dropped round must not go unnoticed
+    assert philox_ints.philox4x32((0, 0, 0, 0), (0, 0), rounds=9) != zo.philox((0, 0, 0, 0), (0, 0))
+
+
+def _closed_form(ra, rb):
+    u = (2 * (ra >> 9) + 1) / 2.0**24
+    ang = ((rb >> 30) + ((rb >> 6) & 0xFFFFFF) / 2.0**24) * (np.pi / 2)
+    rho = np.sqrt(-2.0 * np.log(u))
+    return rho * np.cos(ang), rho * np.sin(ang)
+
+
+def test_counter_layout_words_to_elements():
+    # element 4j+l of tensor t under seed s comes from Philox(counter=(j lo, j hi, t, 0), key=(s lo, s hi)):
+    # words (0,1) -> elements 4j, 4j+1 ; words (2,3) -> elements 4j+2, 4j+3
+    for seed, t, j in [(42, 0, 0), (42, 0, 1), (42, 1, 0), (2**40 + 5, 33, 2**31 + 3), (7, 66, 12345)]:
+        w = philox_ints.words_for(seed, t, j)
+        z = zo.z_values(seed, t, 4 * j, 4)
+        for pair in range(2):
+            c0, c1 = _closed_form(w[2 * pair], w[2 * pair + 1])
+            assert abs(z[2 * pair] - c0) < 2e-6 * max(1.0, abs(c0))
+            assert abs(z[2 * pair + 1] - c1) < 2e-6 * max(1.0, abs(c1))
+
+
+def test_normal_pair_matches_closed_form_everywhere():
+    rng = np.random.default_rng(11)
+    ras = list(rng.integers(0, 2**32, 20000)) + [0, 1 << 9, 0xFFFFFFFF, 0xFFFFFE00, 0x80000000, 0x7FFFFFFF]
+    rbs = list(rng.integers(0, 2**32, 20000)) + [0, 0x3FFFFFC0, 0x20000000, 0x1FFFFFC0, 0x40000000, 0xFFFFFFFF]
+    worst = 0.0
+    for ra, rb in zip(ras, rbs):
+        ra, rb = int(ra), int(rb)
+        z0, z1 = zo.normal_pair(ra, rb)
+        c0, c1 = _closed_form(ra, rb)
+        rho = np.hypot(c0, c1)
+        # error relative to the radius: a few fp32 ulps
+        worst = max(worst, abs(z0 - c0) / rho, abs(z1 - c1) / rho)
+    assert worst < 4 * 2.0**-23, worst
+
+
+def test_normal_radius_identity_and_extremes():
+    # z0^2 + z1^2 = -2 ln u, largest radius at u = 2^-24, smallest at u = 1 - 2^-24
+    for ra, rb in [(0, 0x12345678), (0xFFFFFFFF, 0x9ABCDEF0), (0x40000000, 0)]:
+        z0, z1 = zo.normal_pair(ra, rb)
+        u = (2 * (ra >> 9) + 1) / 2.0**24
+        assert abs((float(z0)**2 + float(z1)**2) / (-2 * np.log(u)) - 1) < 1e-6
+    z0, z1 = zo.normal_pair(0, 0)
+    assert abs(float(z0) - np.sqrt(2 * 24 * np.log(2))) < 1e-5 and z1 == 0
+    # quadrants: rb = q<<30 with zero fraction gives the four axis directions
+    dirs = [np.sign(zo.normal_pair(0, q << 30)).tolist() for q in range(4)]
+    assert [[float(a) + 0.0, float(b) + 0.0] for a, b in dirs] == [[1, 0], [0, 1], [-1, 0], [0, -1]]
+
+
+def test_z_is_standard_normal():
+    z = zo.z_values(123, 5, 0, 1 << 22).astype(np.float64)
+    n = z.size
+    assert abs(z.mean()) < 5 / np.sqrt(n)
+    assert abs(z.var() - 1) < 5 * np.sqrt(2 / n)
+    assert abs(stats.skew(z)) < 5 * np.sqrt(6 / n)
+    assert abs(stats.kurtosis(z)) < 5 * np.sqrt(24 / n)
+    assert stats.kstest(z[:200000], "norm").pvalue > 1e-3
+    # neighbours (same pair, adjacent pairs, adjacent blocks) are uncorrelated
+    for lag in (1, 2, 4):
+        assert abs(np.mean(z[:-lag] * z[lag:])) < 5 / np.sqrt(n)
+
+
+def test_same_seed_same_z_any_chunking():
+    full = zo.z_values(42, 3, 0, 1003)
+    again = zo.z_values(42, 3, 0, 1003)
+    assert full.tobytes() == again.tobytes()
+    pieces = [zo.z_values(42, 3, a, b - a) for a, b in [(0, 1), (1, 2), (2, 7), (7, 8), (8, 513), (513, 1003)]]
+    assert np.concatenate(pieces).tobytes() == full.tobytes()
+    assert zo.z_values(42, 3, 0, 0).size == 0
+    assert zo.z_values(43, 3, 0, 64).tobytes() != full[:64].tobytes()
+    assert zo.z_values(42, 4, 0, 64).tobytes() != full[:64].tobytes()
+    assert zo.z_values(42, 3, 0, 64, stream_tag=1).tobytes() != full[:64].tobytes()
+    # beyond 2^32 elements the high counter word takes over
+    hi = zo.z_values(42, 3, 2**34, 8)
+    w = philox_ints.words_for(42, 3, 2**32)
+    assert abs(hi[0] - _closed_form(w[0], w[1])[0]) < 1e-5
+
+
+def _bits_sample(rng, n):
+    x = rng.integers(0, 2**32, n, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    near = rng.standard_normal(n).astype(np.float32) * np.float32(6e-5)   # half subnormals
+    ties = (rng.integers(0, 2**16, n, dtype=np.uint64).astype(np.uint32) << 16 | 0x8000).view(np.float32)
+    big = rng.standard_normal(n).astype(np.float32) * np.float32(65504)
+    x = np.concatenate([x, near, ties, big, np.float32([0.0, -0.0, 65504, 65520, 65519.99, 2.0**-24, 2.0**-25,
+                                                       1.5 * 2.0**-25, 2.0**-14, np.inf, -np.inf])])
+    return x[np.isfinite(x) | np.isinf(x)]
+
+
+def test_half_and_bfloat_rounding_match_library_casts():
+    import torch
+    rng = np.random.default_rng(3)
+    x = _bits_sample(rng, 50000)
+    x = x[~np.isnan(x)]
+    lib = zo._clib()
+    with np.errstate(over="ignore"):
+        want16 = x.astype(np.float16).view(np.uint16)
+    got16 = np.array([lib.zo_oracle_f32_to_f16(float(v)) for v in x], dtype=np.uint16)
+    assert np.array_equal(got16, want16)
+    wantb = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    gotb = np.array([lib.zo_oracle_f32_to_bf16(float(v)) for v in x], dtype=np.uint16)
+    assert np.array_equal(gotb, wantb)
+    assert np.array_equal(zo.to_storage(x, zo.BF16), wantb)
+    # widening is exact
+    h = np.arange(0, 2**16, dtype=np.uint16)
+    back = np.array([lib.zo_oracle_f16_to_f32(int(v)) for v in h], dtype=np.float32)
+    ref = h.view(np.float16).astype(np.float32)
+    ok = ~np.isnan(ref)
+    assert np.array_equal(back[ok], ref[ok])
+
+
+def _exact_fma_error_ok(scale, z, theta, result):
+    """|result - (scale*z + theta)| <= half an ulp of result, in exact rationals."""
+    exact = Fraction(float(scale)) * Fraction(float(z)) + Fraction(float(theta))
+    r = float(result)
+    ulp = Fraction(float(np.spacing(np.float32(abs(r)) if r != 0 else np.float32(0))))
+    return abs(Fraction(r) - exact) <= ulp / 2
+
+
+def test_axpy_fp32_is_a_correctly_rounded_fma():
+    rng = np.random.default_rng(5)
+    theta = (0.02 * rng.standard_normal(600)).astype(np.float32)
+    z = zo.z_values(9, 17, 0, 600)
+    for scale in (np.float32(1e-3), np.float32(-2e-3), np.float32(-3.3e-6)):
+        out = zo.axpy_z(theta, zo.FP32, 9, 17, scale)
+        assert all(_exact_fma_error_ok(scale, z[i], theta[i], out[i]) for i in range(600))
+    # a separately rounded multiply then add differs somewhere: the fused form is what is specified
+    unfused = (np.float32(1e-3) * z).astype(np.float32) + theta
+    assert np.any(unfused != zo.axpy_z(theta, zo.FP32, 9, 17, np.float32(1e-3)))
+
+
+@pytest.mark.parametrize("dtype", [zo.BF16, zo.FP16])
+def test_axpy_low_precision_rounds_the_fp32_fma(dtype):
+    rng = np.random.default_rng(6)
+    x32 = (0.02 * rng.standard_normal(5000)).astype(np.float32)
+    theta = zo.to_storage(x32, dtype)
+    wide = zo.widen(theta, dtype).astype(np.float32)
+    z = zo.z_values(1, 2, 0, 5000)
+    scale = np.float32(1e-3)
+    # fp64 product-sum of fp32 values rounded to fp32 equals the fp32 fma except on
+    # double-rounding ties, which this sample is checked not to contain
+    f32 = (np.float64(scale) * z.astype(np.float64) + wide.astype(np.float64)).astype(np.float32)
+    want = zo.to_storage(f32, dtype)
+    got = zo.axpy_z(theta, dtype, 1, 2, scale)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("dtype", [zo.FP32, zo.BF16, zo.FP16])
+def test_zero_scale_and_slices(dtype):
+    rng = np.random.default_rng(8)
+    theta = zo.to_storage((0.02 * rng.standard_normal(1001)).astype(np.float32), dtype)
+    assert zo.axpy_z(theta, dtype, 4, 4, 0.0).tobytes() == theta.tobytes()
+    whole = zo.axpy_z(theta, dtype, 4, 4, 1e-3)
+    parts = [zo.axpy_z(theta[a:b], dtype, 4, 4, 1e-3, first=a) for a, b in [(0, 3), (3, 3), (3, 510), (510, 1001)]]
+    assert np.concatenate(parts).tobytes() == whole.tobytes()
+
+
+def test_perturb_cycle_returns_within_one_ulp_fp32():
+    rng = np.random.default_rng(9)
+    theta = (0.02 * rng.standard_normal(20000)).astype(np.float32)
+    t = theta.copy()
+    eps = np.float32(1e-3)
+    for s in (eps, -2 * eps, eps):
+        zo.axpy_z(t, zo.FP32, 42, 0, s, out=t)
+    # each of the three roundings is at most half an ulp at magnitude <= |theta| + 2 eps |z|
+    bound = 1.5 * np.spacing(np.abs(theta) + 2 * eps * np.abs(zo.z_values(42, 0, 0, 20000)))
+    assert np.all(np.abs(t - theta) <= bound)
+    assert np.mean(t == theta) > 0.3
