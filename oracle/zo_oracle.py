@@ -63,6 +63,7 @@ def _clib():
         lib.zo_oracle_philox4x32_10.argtypes = [u32p, u32p, u32p]
         lib.zo_oracle_normal_pair.argtypes = [ctypes.c_uint32, ctypes.c_uint32,
                                               ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+        lib.zo_oracle_normal_pairs.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
         lib.zo_oracle_z.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint64,
                                     ctypes.c_uint64, ctypes.c_void_p]
         lib.zo_oracle_axpy_z.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64,
@@ -92,6 +93,15 @@ def normal_pair(ra, rb):
     a, b = ctypes.c_float(), ctypes.c_float()
     _clib().zo_oracle_normal_pair(ra, rb, ctypes.byref(a), ctypes.byref(b))
     return np.float32(a.value), np.float32(b.value)
+
+
+def normal_pairs(words):
+    """The transform over a uint32 array of word pairs (even length) -> fp32 array of the same length."""
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    assert words.size % 2 == 0
+    out = np.empty(words.size, dtype=np.float32)
+    _clib().zo_oracle_normal_pairs(words.ctypes.data, out.ctypes.data, words.size // 2)
+    return out
 
 
 def z_values(seed, tensor_id, first, n, stream_tag=0):
@@ -189,14 +199,10 @@ def embed(tokens, w_tok, w_pos):
     return w_tok[tokens] + w_pos[:S][None, :, :]
 
 
-def block_forward(h, p, n_heads, ln_eps):
-    """One pre-LN decoder block.  `p` maps the names of BLOCK_TENSORS to fp64 arrays."""
-    B, S, d = h.shape
+def causal_attention(q, k, v, n_heads):
+    """softmax(q k^T / sqrt(d_head), keys <= query) v per head; q, k, v are [B, S, d]."""
+    B, S, d = q.shape
     dh = d // n_heads
-    a = layer_norm(h, p["ln1_g"], p["ln1_b"], ln_eps)
-    q = a @ p["wq"] + p["bq"]
-    k = a @ p["wk"] + p["bk"]
-    v = a @ p["wv"] + p["bv"]
     q = q.reshape(B, S, n_heads, dh).transpose(0, 2, 1, 3)
     k = k.reshape(B, S, n_heads, dh).transpose(0, 2, 1, 3)
     v = v.reshape(B, S, n_heads, dh).transpose(0, 2, 1, 3)
@@ -206,7 +212,16 @@ def block_forward(h, p, n_heads, ln_eps):
     scores = scores - scores.max(axis=-1, keepdims=True)
     prob = np.exp(scores)
     prob = prob / prob.sum(axis=-1, keepdims=True)
-    o = (prob @ v).transpose(0, 2, 1, 3).reshape(B, S, d)
+    return (prob @ v).transpose(0, 2, 1, 3).reshape(B, S, d)
+
+
+def block_forward(h, p, n_heads, ln_eps):
+    """One pre-LN decoder block.  `p` maps the names of BLOCK_TENSORS to fp64 arrays."""
+    a = layer_norm(h, p["ln1_g"], p["ln1_b"], ln_eps)
+    q = a @ p["wq"] + p["bq"]
+    k = a @ p["wk"] + p["bk"]
+    v = a @ p["wv"] + p["bv"]
+    o = causal_attention(q, k, v, n_heads)
     h = h + o @ p["wo"] + p["bo"]
     f = layer_norm(h, p["ln2_g"], p["ln2_b"], ln_eps)
     f = np.maximum(f @ p["w1"] + p["b1"], 0.0)

@@ -137,6 +137,14 @@ void zo_oracle_normal_pair(uint32_t ra, uint32_t rb, float *z0, float *z1)
     *z1 = rho * s;
 }
 
+/* The transform alone over an array of word pairs: z[2i], z[2i+1] from words[2i], words[2i+1]. */
+void zo_oracle_normal_pairs(const uint32_t *words, float *z, uint64_t n_pairs)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n_pairs; ++i)
+        zo_oracle_normal_pair(words[2 * i], words[2 * i + 1], &z[2 * i], &z[2 * i + 1]);
+}
+
 /* z for the elements [first, first+n) of one tensor.  Words (r0,r1) of block j
  * give elements 4j and 4j+1, words (r2,r3) give 4j+2 and 4j+3. */
 void zo_oracle_z(uint64_t seed, uint32_t tensor_id, uint32_t stream_tag, uint64_t first, uint64_t n, float *out)

@@ -1,0 +1,763 @@
+// C-ABI of libzo (see include/zo.h): argument checks, workspace layout, and the host-side
+// schedule of one ZO-SGD step -- DistZO2 App. A, Alg. 1 (literal order), Alg. 2 (per-module
+// dual forward with the deferred update) and Alg. 3 (upload / compute / offload overlap).
+#include "../../include/zo.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "zo_kernels.h"
+#include "zo_types.hip.h"
+
+using namespace zo;
+
+// ------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+#define ZO_HIP(expr)                                                                                   \
+    do {                                                                                               \
+        hipError_t e__ = (expr);                                                                       \
+        if (e__ != hipSuccess) return fail(ZO_EHIP, "%s failed: %s", #expr, hipGetErrorString(e__)); \
+    } while (0)
+#define ZO_TRY(expr)                 \
+    do {                             \
+        int r__ = (expr);            \
+        if (r__ != ZO_OK) return r__; \
+    } while (0)
+
+extern "C" const char *zo_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------ model
+namespace {
+
+constexpr int kPerBlock = 16;
+enum { T_LN1G, T_LN1B, T_WQ, T_BQ, T_WK, T_BK, T_WV, T_BV, T_WO, T_BO, T_LN2G, T_LN2B, T_W1, T_B1, T_W2, T_B2 };
+enum SlotState { SLOT_EMPTY, SLOT_UPLOADED, SLOT_COMPUTED };
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// Element offsets of the 16 tensors inside a block as stored (canonical order), and of the
+// staged (transposed, q|k|v fused) copies the forward reads.
+struct BlockLayout {
+    size_t src_off[kPerBlock];   // in elements, canonical storage order
+    uint32_t rows[kPerBlock], cols[kPerBlock];
+    size_t total;                // elements per block
+    // staged layout (elements): ln1_g, ln1_b, wqkv_t[3d,d], bqkv[3d], wo_t[d,d], bo, ln2_g, ln2_b, w1_t[F,d], b1, w2_t[d,F], b2
+    size_t st_ln1g, st_ln1b, st_wqkv, st_bqkv, st_wo, st_bo, st_ln2g, st_ln2b, st_w1, st_b1, st_w2, st_b2;
+};
+
+BlockLayout make_layout(int d, int f)
+{
+    BlockLayout L{};
+    const uint32_t r[kPerBlock] = {1, 1, (uint32_t)d, 1, (uint32_t)d, 1, (uint32_t)d, 1, (uint32_t)d, 1, 1, 1, (uint32_t)d, 1, (uint32_t)f, 1};
+    const uint32_t c[kPerBlock] = {(uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d,
+                                   (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)f, (uint32_t)f, (uint32_t)d, (uint32_t)d};
+    size_t off = 0;
+    for (int i = 0; i < kPerBlock; ++i) {
+        L.rows[i] = r[i]; L.cols[i] = c[i]; L.src_off[i] = off; off += (size_t)r[i] * c[i];
+    }
+    L.total = off;
+    size_t o = 0;
+    const size_t D = d, F = f;
+    L.st_ln1g = o; o += D; L.st_ln1b = o; o += D;
+    L.st_wqkv = o; o += 3 * D * D; L.st_bqkv = o; o += 3 * D;
+    L.st_wo = o; o += D * D; L.st_bo = o; o += D;
+    L.st_ln2g = o; o += D; L.st_ln2b = o; o += D;
+    L.st_w1 = o; o += D * F; L.st_b1 = o; o += F;
+    L.st_w2 = o; o += F * D; L.st_b2 = o; o += D;
+    return L;
+}
+
+struct Workspace {           // byte offsets into the caller's workspace
+    size_t descs, resid, xbuf, qkv, att, mid, logits, stage[2], e_pm[2], pos_pm[2], lnf_pm[2], target, row_loss, scalars,
+        slot[2], total;
+    int logits_rows;
+};
+
+int check_cfg(const zo_config *c)
+{
+    if (!c) return fail(ZO_EINVAL, "cfg is NULL");
+    if (c->n_layers < 1 || c->d_model < 8 || c->n_heads < 1 || c->d_ffn < 8 || c->vocab < 2 || c->max_pos < 1)
+        return fail(ZO_EINVAL, "non-positive model dimension");
+    if (c->d_model % c->n_heads) return fail(ZO_EINVAL, "d_model %d is not a multiple of n_heads %d", c->d_model, c->n_heads);
+    if (c->d_model % 8 || c->d_ffn % 8) return fail(ZO_EINVAL, "d_model and d_ffn must be multiples of 8");
+    if (c->d_model / c->n_heads > 128) return fail(ZO_EINVAL, "head size above 128 is not supported");
+    if (c->dtype < 0 || c->dtype > 2) return fail(ZO_EINVAL, "dtype %d unknown", c->dtype);
+    if (c->residency != ZO_RESIDENT && c->residency != ZO_STREAMED) return fail(ZO_EINVAL, "residency %d unknown", c->residency);
+    if (!(c->ln_eps > 0.0f)) return fail(ZO_EINVAL, "ln_eps must be positive");
+    return ZO_OK;
+}
+
+Workspace plan_workspace(const zo_config &c, int batch, int seq)
+{
+    Workspace w{};
+    const size_t e = elem_bytes(c.dtype), ab = act_bytes(c.dtype), rb = resid_bytes(c.dtype), cb = acc_bytes(c.dtype);
+    const size_t rows = 2 * (size_t)batch * seq, d = c.d_model, f = c.d_ffn;
+    const BlockLayout L = make_layout(c.d_model, c.d_ffn);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    w.descs = take(sizeof(TensorDesc) * (4 + (size_t)kPerBlock * c.n_layers));
+    w.resid = take(rows * d * rb);
+    w.xbuf = take(rows * d * ab);
+    w.qkv = take(rows * 3 * d * ab);
+    w.att = take(rows * d * ab);
+    w.mid = take(rows * f * ab);
+    size_t lr = rows < 2048 ? rows : 2048;       // logits are produced and reduced in row chunks
+    w.logits_rows = (int)lr;
+    w.logits = take(lr * (size_t)c.vocab * cb);
+    for (int s = 0; s < 2; ++s) w.stage[s] = take(L.total * e);
+    for (int s = 0; s < 2; ++s) w.e_pm[s] = take((size_t)c.vocab * d * e);
+    for (int s = 0; s < 2; ++s) w.pos_pm[s] = take((size_t)c.max_pos * d * e);
+    for (int s = 0; s < 2; ++s) w.lnf_pm[s] = take(2 * d * e);
+    w.target = take(rows * sizeof(int32_t));
+    w.row_loss = take(rows * sizeof(double));
+    w.scalars = take(256);
+    if (c.residency == ZO_STREAMED)
+        for (int s = 0; s < 2; ++s) w.slot[s] = take(L.total * e);
+    w.total = o;
+    return w;
+}
+
+}  // namespace
+
+struct zo_model {
+    zo_config cfg;
+    int n_tensors, max_batch, max_seq;
+    BlockLayout lay;
+    Workspace wsp;
+    char *ws;
+    std::vector<void *> tptr;
+    std::vector<TensorDesc> descs;     // host copy; device copy at ws + wsp.descs
+    uint64_t total_chunks;
+    hipStream_t compute, upload, download;
+    bool own_download;
+    bool use_mfma;
+    // device scalars
+    double *loss_pm, *g;
+    float *s_cur, *s_pending;
+    uint32_t *flags;
+    // streamed state
+    hipEvent_t ev_uploaded[2], ev_staged[2], ev_written[2];
+    int slot_block[2];
+    SlotState slot_state[2];
+    bool slot_dirty[2];
+    bool pending;
+    uint64_t pending_seed;
+    bool step_open;
+    int next_block;
+    uint64_t step_seed;
+    float step_eps;
+    int step_batch, step_seq;
+};
+
+namespace {
+
+template <typename T> T *wsp_ptr(zo_model *m, size_t off) { return (T *)(m->ws + off); }
+
+size_t tensor_numel(const zo_config &c, const BlockLayout &L, int t)
+{
+    const int last = 2 + kPerBlock * c.n_layers;
+    if (t == 0) return (size_t)c.vocab * c.d_model;
+    if (t == 1) return (size_t)c.max_pos * c.d_model;
+    if (t >= last) return (size_t)c.d_model;
+    const int k = (t - 2) % kPerBlock;
+    return (size_t)L.rows[k] * L.cols[k];
+}
+
+bool is_block_tensor(const zo_model *m, int t) { return t >= 2 && t < 2 + kPerBlock * m->cfg.n_layers; }
+
+int check_batch(const zo_model *m, const int32_t *tokens, int batch, int seq)
+{
+    if (!tokens) return fail(ZO_EINVAL, "tokens is NULL");
+    if (batch < 1 || seq < 2) return fail(ZO_EINVAL, "need batch >= 1 and seq >= 2 (got %d x %d)", batch, seq);
+    if (seq > m->cfg.max_pos) return fail(ZO_EINVAL, "seq %d exceeds max_pos %d", seq, m->cfg.max_pos);
+    if ((size_t)batch * seq > (size_t)m->max_batch * m->max_seq)
+        return fail(ZO_EINVAL, "batch %d x seq %d exceeds the %d x %d the workspace was sized for", batch, seq, m->max_batch, m->max_seq);
+    return ZO_OK;
+}
+
+// in-place theta <- rn(fma(scale, z, theta)) over tensors [first, first + n)
+int axpy_range(zo_model *m, int first, int n, uint64_t seed, float scale, const float *dev_scale)
+{
+    if (n <= 0) return ZO_OK;
+    const uint64_t c0 = m->descs[first].first_chunk;
+    const uint64_t c1 = first + n < m->n_tensors ? m->descs[first + n].first_chunk : m->total_chunks;
+    ZO_HIP(launch_axpy_multi(wsp_ptr<TensorDesc>(m, m->wsp.descs) + first, n, c0, c1 - c0, m->cfg.dtype, seed, scale, dev_scale,
+                             m->compute));
+    return ZO_OK;
+}
+
+struct BlockPtrs {   // staged parameter pointers of one block, per sign
+    const char *base[2];
+};
+
+// Stage the embeddings and the final LayerNorm: W+- copies (fused) or nothing (literal reads theta itself).
+int stage_globals(zo_model *m, int seq, uint64_t seed, float eps)
+{
+    const zo_config &c = m->cfg;
+    StageBatch b{};
+    const int lnf = 2 + kPerBlock * c.n_layers;
+    const size_t e = elem_bytes(c.dtype);
+    stage_batch_add(b, m->tptr[0], m->ws + m->wsp.e_pm[0], m->ws + m->wsp.e_pm[1], c.vocab, c.d_model, 0, false);
+    stage_batch_add(b, m->tptr[1], m->ws + m->wsp.pos_pm[0], m->ws + m->wsp.pos_pm[1], seq, c.d_model, 1, false);
+    stage_batch_add(b, m->tptr[lnf], m->ws + m->wsp.lnf_pm[0], m->ws + m->wsp.lnf_pm[1], 1, c.d_model, lnf, false);
+    stage_batch_add(b, m->tptr[lnf + 1], m->ws + m->wsp.lnf_pm[0] + c.d_model * e, m->ws + m->wsp.lnf_pm[1] + c.d_model * e, 1,
+                    c.d_model, lnf + 1, false);
+    ZO_HIP(launch_stage(b, c.dtype, seed, eps, false, m->compute));
+    return ZO_OK;
+}
+
+// Stage one block from `src_base` (16 tensors in canonical order) into the per-sign scratch.
+int stage_block(zo_model *m, int layer, const char *src_base, uint64_t seed, float eps, bool single)
+{
+    const zo_config &c = m->cfg;
+    const BlockLayout &L = m->lay;
+    const size_t e = elem_bytes(c.dtype), D = c.d_model;
+    char *sp = m->ws + m->wsp.stage[0], *sm = m->ws + m->wsp.stage[1];
+    const int t0 = 2 + kPerBlock * layer;
+    StageBatch b{};
+    auto add = [&](int k, size_t dst_off, bool tr) {
+        stage_batch_add(b, src_base + L.src_off[k] * e, sp + dst_off * e, sm + dst_off * e, L.rows[k], L.cols[k], t0 + k, tr);
+    };
+    add(T_LN1G, L.st_ln1g, false); add(T_LN1B, L.st_ln1b, false);
+    add(T_WQ, L.st_wqkv, true); add(T_WK, L.st_wqkv + D * D, true); add(T_WV, L.st_wqkv + 2 * D * D, true);
+    add(T_BQ, L.st_bqkv, false); add(T_BK, L.st_bqkv + D, false); add(T_BV, L.st_bqkv + 2 * D, false);
+    add(T_WO, L.st_wo, true); add(T_BO, L.st_bo, false);
+    add(T_LN2G, L.st_ln2g, false); add(T_LN2B, L.st_ln2b, false);
+    add(T_W1, L.st_w1, true); add(T_B1, L.st_b1, false);
+    add(T_W2, L.st_w2, true); add(T_B2, L.st_b2, false);
+    ZO_HIP(launch_stage(b, c.dtype, seed, eps, single, m->compute));
+    return ZO_OK;
+}
+
+// One decoder block on the staged parameters; activations in the workspace.
+int block_forward(zo_model *m, int n_sign, int batch, int seq)
+{
+    const zo_config &c = m->cfg;
+    const BlockLayout &L = m->lay;
+    const size_t e = elem_bytes(c.dtype);
+    const int m_half = batch * seq, d = c.d_model, f = c.d_ffn, dt = c.dtype;
+    const char *P = m->ws + m->wsp.stage[0], *M = m->ws + m->wsp.stage[1];
+    void *resid = m->ws + m->wsp.resid, *x = m->ws + m->wsp.xbuf, *qkv = m->ws + m->wsp.qkv, *att = m->ws + m->wsp.att,
+         *mid = m->ws + m->wsp.mid;
+    hipStream_t s = m->compute;
+    auto at = [&](const char *base, size_t off) { return (const void *)(base + off * e); };
+    ZO_HIP(launch_layernorm(resid, at(P, L.st_ln1g), at(M, L.st_ln1g), at(P, L.st_ln1b), at(M, L.st_ln1b), x, dt, n_sign, m_half, d,
+                            c.ln_eps, s));
+    ZO_HIP(launch_linear(x, at(P, L.st_wqkv), at(M, L.st_wqkv), at(P, L.st_bqkv), at(M, L.st_bqkv), qkv, dt, n_sign, m_half, 3 * d, d, 0,
+                         m->use_mfma, s));
+    ZO_HIP(launch_attention(qkv, att, dt, n_sign * batch, seq, c.n_heads, d / c.n_heads, m->use_mfma, s));
+    ZO_HIP(launch_linear(att, at(P, L.st_wo), at(M, L.st_wo), at(P, L.st_bo), at(M, L.st_bo), resid, dt, n_sign, m_half, d, d, 2,
+                         m->use_mfma, s));
+    ZO_HIP(launch_layernorm(resid, at(P, L.st_ln2g), at(M, L.st_ln2g), at(P, L.st_ln2b), at(M, L.st_ln2b), x, dt, n_sign, m_half, d,
+                            c.ln_eps, s));
+    ZO_HIP(launch_linear(x, at(P, L.st_w1), at(M, L.st_w1), at(P, L.st_b1), at(M, L.st_b1), mid, dt, n_sign, m_half, f, d, 1,
+                         m->use_mfma, s));
+    ZO_HIP(launch_linear(mid, at(P, L.st_w2), at(M, L.st_w2), at(P, L.st_b2), at(M, L.st_b2), resid, dt, n_sign, m_half, d, f, 2,
+                         m->use_mfma, s));
+    return ZO_OK;
+}
+
+// LM head (tied) + cross entropy over row chunks.  x: final-LayerNormed activations [n_sign*m_half, d].
+int lmhead_ce(hipStream_t s, const void *x, const void *e_p, const void *e_m, const int32_t *target, double *row_loss, void *logits,
+              int logits_rows, int dtype, int n_sign, int m_half, int d, int vocab, bool use_mfma)
+{
+    const size_t ab = act_bytes(dtype);
+    for (int sign = 0; sign < n_sign; ++sign) {
+        const void *wt = sign ? e_m : e_p;
+        for (int r0 = 0; r0 < m_half; r0 += logits_rows) {
+            const int nr = m_half - r0 < logits_rows ? m_half - r0 : logits_rows;
+            const size_t row = (size_t)sign * m_half + r0;
+            const char *xa = (const char *)x + row * d * ab;
+            ZO_HIP(launch_linear(xa, wt, wt, nullptr, nullptr, logits, dtype, 1, nr, vocab, d, 3, use_mfma, s));
+            ZO_HIP(launch_ce_rows(logits, target + row, row_loss + row, dtype, nr, vocab, s));
+        }
+    }
+    return ZO_OK;
+}
+
+int head_and_loss(zo_model *m, int n_sign, int batch, int seq, const void *e_p, const void *e_m, const void *lnf_p,
+                  const void *lnf_m, double *loss_out)
+{
+    const zo_config &c = m->cfg;
+    const size_t e = elem_bytes(c.dtype);
+    const int m_half = batch * seq, d = c.d_model;
+    void *resid = m->ws + m->wsp.resid, *x = m->ws + m->wsp.xbuf;
+    int32_t *target = wsp_ptr<int32_t>(m, m->wsp.target);
+    double *row_loss = wsp_ptr<double>(m, m->wsp.row_loss);
+    ZO_HIP(launch_layernorm(resid, lnf_p, lnf_m, (const char *)lnf_p + d * e, (const char *)lnf_m + d * e, x, c.dtype, n_sign, m_half, d,
+                            c.ln_eps, m->compute));
+    ZO_TRY(lmhead_ce(m->compute, x, e_p, e_m, target, row_loss, m->ws + m->wsp.logits, m->wsp.logits_rows, c.dtype, n_sign, m_half, d,
+                     c.vocab, m->use_mfma));
+    ZO_HIP(launch_loss_reduce(row_loss, n_sign, m_half, batch * (seq - 1), loss_out, m->compute));
+    return ZO_OK;
+}
+
+int embed(zo_model *m, const int32_t *tokens, int n_sign, int batch, int seq, const void *e_p, const void *e_m, const void *pos_p,
+          const void *pos_m)
+{
+    ZO_HIP(launch_embed(tokens, e_p, e_m, pos_p, pos_m, m->ws + m->wsp.resid, wsp_ptr<int32_t>(m, m->wsp.target), m->flags,
+                        m->cfg.dtype, n_sign, batch, seq, m->cfg.d_model, m->cfg.vocab, m->compute));
+    return ZO_OK;
+}
+
+// Both signs in one batched pass over staged W+-; theta untouched.
+int forward_fused_resident(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t seed, float eps)
+{
+    const zo_config &c = m->cfg;
+    ZO_TRY(stage_globals(m, seq, seed, eps));
+    const char *ep = m->ws + m->wsp.e_pm[0], *em = m->ws + m->wsp.e_pm[1];
+    ZO_TRY(embed(m, tokens, 2, batch, seq, ep, em, m->ws + m->wsp.pos_pm[0], m->ws + m->wsp.pos_pm[1]));
+    for (int l = 0; l < c.n_layers; ++l) {
+        ZO_TRY(stage_block(m, l, (const char *)m->tptr[2 + kPerBlock * l], seed, eps, false));
+        ZO_TRY(block_forward(m, 2, batch, seq));
+    }
+    return head_and_loss(m, 2, batch, seq, ep, em, m->ws + m->wsp.lnf_pm[0], m->ws + m->wsp.lnf_pm[1], m->loss_pm);
+}
+
+// One forward of theta as it stands (literal mode), loss into loss_pm[slot].
+int forward_single(zo_model *m, const int32_t *tokens, int batch, int seq, int slot)
+{
+    const zo_config &c = m->cfg;
+    const int lnf = 2 + kPerBlock * c.n_layers;
+    const size_t e = elem_bytes(c.dtype);
+    // the final LayerNorm's gain and bias are separate tensors: gather them side by side
+    StageBatch b{};
+    stage_batch_add(b, m->tptr[lnf], m->ws + m->wsp.lnf_pm[0], nullptr, 1, c.d_model, lnf, false);
+    stage_batch_add(b, m->tptr[lnf + 1], m->ws + m->wsp.lnf_pm[0] + c.d_model * e, nullptr, 1, c.d_model, lnf + 1, false);
+    ZO_HIP(launch_stage(b, c.dtype, 0, 0.0f, true, m->compute));
+    ZO_TRY(embed(m, tokens, 1, batch, seq, m->tptr[0], m->tptr[0], m->tptr[1], m->tptr[1]));
+    for (int l = 0; l < c.n_layers; ++l) {
+        ZO_TRY(stage_block(m, l, (const char *)m->tptr[2 + kPerBlock * l], 0, 0.0f, true));
+        ZO_TRY(block_forward(m, 1, batch, seq));
+    }
+    return head_and_loss(m, 1, batch, seq, m->tptr[0], m->tptr[0], m->ws + m->wsp.lnf_pm[0], m->ws + m->wsp.lnf_pm[0],
+                         m->loss_pm + slot);
+}
+
+int read_back(zo_model *m, double *host_g, double *host_loss_pm)
+{
+    if (!host_g && !host_loss_pm) return ZO_OK;
+    double tmp[3];
+    ZO_HIP(hipMemcpyAsync(tmp, m->loss_pm, 3 * sizeof(double), hipMemcpyDeviceToHost, m->compute));   // loss_pm[2], g adjacent
+    ZO_HIP(hipStreamSynchronize(m->compute));
+    if (host_loss_pm) { host_loss_pm[0] = tmp[0]; host_loss_pm[1] = tmp[1]; }
+    if (host_g) *host_g = tmp[2];
+    return ZO_OK;
+}
+
+// ---- streamed model: Alg. 3's three operations on a block ----
+int stream_prefetch(zo_model *m, int block)
+{
+    const int slot = block & 1;
+    if (m->slot_state[slot] == SLOT_UPLOADED)
+        return fail(ZO_ESTATE, "slot %d still holds block %d awaiting COMPUTE", slot, m->slot_block[slot]);
+    if (m->slot_state[slot] == SLOT_COMPUTED && m->slot_dirty[slot])
+        return fail(ZO_ESTATE, "block %d was updated in slot %d and has not been written back", m->slot_block[slot], slot);
+    const size_t bytes = m->lay.total * elem_bytes(m->cfg.dtype);
+    // the slot is free once its previous occupant was staged (and, if updated, written back)
+    ZO_HIP(hipStreamWaitEvent(m->upload, m->ev_staged[slot], 0));
+    ZO_HIP(hipStreamWaitEvent(m->upload, m->ev_written[slot], 0));
+    ZO_HIP(hipMemcpyAsync(m->ws + m->wsp.slot[slot], m->tptr[2 + kPerBlock * block], bytes, hipMemcpyHostToDevice, m->upload));
+    ZO_HIP(hipEventRecord(m->ev_uploaded[slot], m->upload));
+    m->slot_block[slot] = block;
+    m->slot_state[slot] = SLOT_UPLOADED;
+    m->slot_dirty[slot] = false;
+    return ZO_OK;
+}
+
+// wait for the upload, apply the pending update, optionally stage + forward
+int stream_compute(zo_model *m, int block, bool forward)
+{
+    const int slot = block & 1;
+    if (m->slot_state[slot] != SLOT_UPLOADED || m->slot_block[slot] != block)
+        return fail(ZO_ESTATE, "block %d was not prefetched", block);
+    ZO_HIP(hipStreamWaitEvent(m->compute, m->ev_uploaded[slot], 0));
+    if (m->pending) {
+        ZO_TRY(axpy_range(m, 2 + kPerBlock * block, kPerBlock, m->pending_seed, 0.0f, m->s_pending));
+        m->slot_dirty[slot] = true;
+    }
+    if (forward) ZO_TRY(stage_block(m, block, m->ws + m->wsp.slot[slot], m->step_seed, m->step_eps, false));
+    ZO_HIP(hipEventRecord(m->ev_staged[slot], m->compute));
+    if (forward) ZO_TRY(block_forward(m, 2, m->step_batch, m->step_seq));
+    m->slot_state[slot] = SLOT_COMPUTED;
+    return ZO_OK;
+}
+
+int stream_writeback(zo_model *m, int block)
+{
+    const int slot = block & 1;
+    if (m->slot_state[slot] != SLOT_COMPUTED || m->slot_block[slot] != block)
+        return fail(ZO_ESTATE, "block %d is not computed in slot %d", block, slot);
+    if (m->slot_dirty[slot]) {
+        const size_t bytes = m->lay.total * elem_bytes(m->cfg.dtype);
+        ZO_HIP(hipStreamWaitEvent(m->download, m->ev_staged[slot], 0));
+        ZO_HIP(hipMemcpyAsync(m->tptr[2 + kPerBlock * block], m->ws + m->wsp.slot[slot], bytes, hipMemcpyDeviceToHost, m->download));
+        ZO_HIP(hipEventRecord(m->ev_written[slot], m->download));
+        m->slot_dirty[slot] = false;
+    }
+    return ZO_OK;
+}
+
+int stream_begin(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t seed, float eps)
+{
+    if (m->step_open) return fail(ZO_ESTATE, "a streamed step is already open");
+    const zo_config &c = m->cfg;
+    const int lnf = 2 + kPerBlock * c.n_layers;
+    m->step_seed = seed; m->step_eps = eps; m->step_batch = batch; m->step_seq = seq;
+    if (m->pending) {   // Alg. 2: the resident modules take last step's update at their visit
+        ZO_TRY(axpy_range(m, 0, 2, m->pending_seed, 0.0f, m->s_pending));
+        ZO_TRY(axpy_range(m, lnf, 2, m->pending_seed, 0.0f, m->s_pending));
+    }
+    ZO_TRY(stage_globals(m, seq, seed, eps));
+    ZO_TRY(embed(m, tokens, 2, batch, seq, m->ws + m->wsp.e_pm[0], m->ws + m->wsp.e_pm[1], m->ws + m->wsp.pos_pm[0],
+                 m->ws + m->wsp.pos_pm[1]));
+    m->step_open = true;
+    m->next_block = 0;
+    return ZO_OK;
+}
+
+int stream_end(zo_model *m, float lr)
+{
+    if (!m->step_open) return fail(ZO_ESTATE, "no streamed step is open");
+    if (m->next_block != m->cfg.n_layers) return fail(ZO_ESTATE, "only %d of %d blocks were computed", m->next_block, m->cfg.n_layers);
+    ZO_TRY(head_and_loss(m, 2, m->step_batch, m->step_seq, m->ws + m->wsp.e_pm[0], m->ws + m->wsp.e_pm[1], m->ws + m->wsp.lnf_pm[0],
+                         m->ws + m->wsp.lnf_pm[1], m->loss_pm));
+    ZO_HIP(launch_g_scalar(m->loss_pm, m->step_eps, lr, m->g, m->s_pending, m->flags, m->compute));
+    m->pending = true;
+    m->pending_seed = m->step_seed;
+    m->step_open = false;
+    return ZO_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ exported calls
+extern "C" size_t zo_workspace_bytes(const zo_config *cfg, int batch, int seq)
+{
+    if (check_cfg(cfg) != ZO_OK || batch < 1 || seq < 2 || seq > cfg->max_pos) return 0;
+    return plan_workspace(*cfg, batch, seq).total;
+}
+
+extern "C" int zo_init_model(const zo_config *cfg, void *const *tensor_ptrs, int n_tensors, void *workspace, size_t workspace_bytes,
+                             int batch, int seq, void *compute_stream, void *copy_stream, zo_model **out)
+{
+    ZO_TRY(check_cfg(cfg));
+    if (!tensor_ptrs || !workspace || !out) return fail(ZO_EINVAL, "NULL argument");
+    if (n_tensors != 4 + kPerBlock * cfg->n_layers)
+        return fail(ZO_EINVAL, "expected %d tensors for %d layers, got %d", 4 + kPerBlock * cfg->n_layers, cfg->n_layers, n_tensors);
+    if (batch < 1 || seq < 2 || seq > cfg->max_pos) return fail(ZO_EINVAL, "bad batch %d x seq %d (max_pos %d)", batch, seq, cfg->max_pos);
+    if ((uintptr_t)workspace % 256) return fail(ZO_EINVAL, "workspace must be 256-byte aligned");
+    const Workspace wsp = plan_workspace(*cfg, batch, seq);
+    if (workspace_bytes < wsp.total) return fail(ZO_ENOMEM, "workspace of %zu bytes given, %zu needed", workspace_bytes, wsp.total);
+    for (int i = 0; i < n_tensors; ++i) {
+        if (!tensor_ptrs[i]) return fail(ZO_EINVAL, "tensor %d is NULL", i);
+        if ((uintptr_t)tensor_ptrs[i] % 16) return fail(ZO_EINVAL, "tensor %d is not 16-byte aligned", i);
+    }
+    if (cfg->residency == ZO_STREAMED && (!copy_stream || copy_stream == compute_stream))
+        return fail(ZO_EINVAL, "a streamed model needs a copy stream distinct from the compute stream");
+
+    zo_model *m = new (std::nothrow) zo_model();
+    if (!m) return fail(ZO_ENOMEM, "host allocation failed");
+    m->cfg = *cfg; m->n_tensors = n_tensors; m->max_batch = batch; m->max_seq = seq;
+    m->lay = make_layout(cfg->d_model, cfg->d_ffn);
+    m->wsp = wsp; m->ws = (char *)workspace;
+    m->tptr.assign(tensor_ptrs, tensor_ptrs + n_tensors);
+    m->compute = (hipStream_t)compute_stream; m->upload = (hipStream_t)copy_stream; m->download = nullptr; m->own_download = false;
+    m->use_mfma = true;
+    const size_t e = elem_bytes(cfg->dtype);
+    if (cfg->residency == ZO_STREAMED) {
+        for (int l = 0; l < cfg->n_layers; ++l)
+            for (int k = 1; k < kPerBlock; ++k)
+                if ((char *)m->tptr[2 + kPerBlock * l + k] != (char *)m->tptr[2 + kPerBlock * l] + m->lay.src_off[k] * e) {
+                    delete m;
+                    return fail(ZO_EINVAL, "streamed model: tensors of block %d are not adjacent in canonical order", l);
+                }
+    }
+    // descriptor table for the in-place passes; streamed block tensors are addressed in their device slot
+    m->descs.resize(n_tensors);
+    uint64_t chunk = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        TensorDesc &d = m->descs[t];
+        void *p = m->tptr[t];
+        if (cfg->residency == ZO_STREAMED && is_block_tensor(m, t)) {
+            const int l = (t - 2) / kPerBlock, k = (t - 2) % kPerBlock;
+            p = m->ws + wsp.slot[l & 1] + m->lay.src_off[k] * e;
+        }
+        d.src = p; d.dst = p; d.numel = tensor_numel(*cfg, m->lay, t); d.first_chunk = chunk; d.tid = (uint32_t)t; d.pad = 0;
+        chunk += (d.numel + kAxpyChunk - 1) / kAxpyChunk;
+    }
+    m->total_chunks = chunk;
+    char *sc = m->ws + wsp.scalars;
+    m->loss_pm = (double *)sc; m->g = (double *)(sc + 16); m->s_cur = (float *)(sc + 24); m->s_pending = (float *)(sc + 28);
+    m->flags = (uint32_t *)(sc + 32);
+    hipError_t err = hipMemcpy(m->ws + wsp.descs, m->descs.data(), sizeof(TensorDesc) * n_tensors, hipMemcpyHostToDevice);
+    if (err == hipSuccess) err = hipMemset(sc, 0, 256);
+    if (err != hipSuccess) { delete m; return fail(ZO_EHIP, "initialising the workspace failed: %s", hipGetErrorString(err)); }
+    m->pending = false; m->step_open = false; m->next_block = 0;
+    for (int s = 0; s < 2; ++s) {
+        m->slot_block[s] = -1; m->slot_state[s] = SLOT_EMPTY; m->slot_dirty[s] = false;
+        m->ev_uploaded[s] = m->ev_staged[s] = m->ev_written[s] = nullptr;
+    }
+    if (cfg->residency == ZO_STREAMED) {
+        err = hipStreamCreateWithFlags(&m->download, hipStreamNonBlocking);
+        m->own_download = err == hipSuccess;
+        for (int s = 0; s < 2 && err == hipSuccess; ++s) {
+            err = hipEventCreateWithFlags(&m->ev_uploaded[s], hipEventDisableTiming);
+            if (err == hipSuccess) err = hipEventCreateWithFlags(&m->ev_staged[s], hipEventDisableTiming);
+            if (err == hipSuccess) err = hipEventCreateWithFlags(&m->ev_written[s], hipEventDisableTiming);
+        }
+        if (err != hipSuccess) { zo_free(m); return fail(ZO_EHIP, "creating streams/events failed: %s", hipGetErrorString(err)); }
+    }
+    *out = m;
+    return ZO_OK;
+}
+
+extern "C" int zo_free(zo_model *m)
+{
+    if (!m) return ZO_OK;
+    if (m->cfg.residency == ZO_STREAMED) {
+        if (m->upload) (void)hipStreamSynchronize(m->upload);
+        if (m->download) (void)hipStreamSynchronize(m->download);
+    }
+    (void)hipStreamSynchronize(m->compute);
+    for (int s = 0; s < 2; ++s) {
+        if (m->ev_uploaded[s]) (void)hipEventDestroy(m->ev_uploaded[s]);
+        if (m->ev_staged[s]) (void)hipEventDestroy(m->ev_staged[s]);
+        if (m->ev_written[s]) (void)hipEventDestroy(m->ev_written[s]);
+    }
+    if (m->own_download) (void)hipStreamDestroy(m->download);
+    delete m;
+    return ZO_OK;
+}
+
+extern "C" int zo_perturb(zo_model *m, uint64_t seed, float scale, int first_tensor, int n_tensors)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    if (first_tensor < 0 || n_tensors < 0 || first_tensor + n_tensors > m->n_tensors)
+        return fail(ZO_EINVAL, "tensor range [%d, %d) outside [0, %d)", first_tensor, first_tensor + n_tensors, m->n_tensors);
+    if (m->cfg.residency == ZO_STREAMED)
+        for (int t = first_tensor; t < first_tensor + n_tensors; ++t)
+            if (is_block_tensor(m, t)) return fail(ZO_ESTATE, "tensor %d lives in host memory; use the streamed step", t);
+    return axpy_range(m, first_tensor, n_tensors, seed, scale, nullptr);
+}
+
+extern "C" int zo_dual_forward(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t seed, float eps, int mode,
+                               double *dev_loss_pm, double *host_loss_pm)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    ZO_TRY(check_batch(m, tokens, batch, seq));
+    if (mode != ZO_MODE_FUSED && mode != ZO_MODE_LITERAL) return fail(ZO_EINVAL, "mode %d unknown", mode);
+    if (!(eps > 0.0f)) return fail(ZO_EINVAL, "eps must be positive");
+    if (m->cfg.residency == ZO_STREAMED) return fail(ZO_ESTATE, "a streamed model runs its forward inside zo_step / zo_stream_*");
+    if (mode == ZO_MODE_FUSED) {
+        ZO_TRY(forward_fused_resident(m, tokens, batch, seq, seed, eps));
+    } else {
+        ZO_TRY(axpy_range(m, 0, m->n_tensors, seed, eps, nullptr));
+        ZO_TRY(forward_single(m, tokens, batch, seq, 0));
+        ZO_TRY(axpy_range(m, 0, m->n_tensors, seed, -2.0f * eps, nullptr));
+        ZO_TRY(forward_single(m, tokens, batch, seq, 1));
+        ZO_TRY(axpy_range(m, 0, m->n_tensors, seed, eps, nullptr));
+    }
+    if (dev_loss_pm) ZO_HIP(hipMemcpyAsync(dev_loss_pm, m->loss_pm, 2 * sizeof(double), hipMemcpyDeviceToDevice, m->compute));
+    if (host_loss_pm) {
+        ZO_HIP(hipMemcpyAsync(host_loss_pm, m->loss_pm, 2 * sizeof(double), hipMemcpyDeviceToHost, m->compute));
+        ZO_HIP(hipStreamSynchronize(m->compute));
+    }
+    return ZO_OK;
+}
+
+extern "C" int zo_step(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t seed, float eps, float lr, int mode,
+                       double *host_g, double *host_loss_pm)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    ZO_TRY(check_batch(m, tokens, batch, seq));
+    if (!(eps > 0.0f)) return fail(ZO_EINVAL, "eps must be positive");
+    if (m->cfg.residency == ZO_RESIDENT) {
+        ZO_TRY(zo_dual_forward(m, tokens, batch, seq, seed, eps, mode, nullptr, nullptr));
+        ZO_HIP(launch_g_scalar(m->loss_pm, eps, lr, m->g, m->s_cur, m->flags, m->compute));
+        ZO_TRY(axpy_range(m, 0, m->n_tensors, seed, 0.0f, m->s_cur));
+        return read_back(m, host_g, host_loss_pm);
+    }
+    if (mode != ZO_MODE_FUSED) return fail(ZO_EINVAL, "a streamed model supports ZO_MODE_FUSED only");
+    // Alg. 3: U(W_{i+1}) is in flight while C(W_i) runs; O(W_i) follows as soon as W_i is staged.
+    ZO_TRY(stream_begin(m, tokens, batch, seq, seed, eps));
+    ZO_TRY(stream_prefetch(m, 0));
+    for (int l = 0; l < m->cfg.n_layers; ++l) {
+        if (l + 1 < m->cfg.n_layers) ZO_TRY(stream_prefetch(m, l + 1));
+        ZO_TRY(stream_compute(m, l, true));
+        m->next_block = l + 1;
+        ZO_TRY(stream_writeback(m, l));
+    }
+    ZO_TRY(stream_end(m, lr));
+    return read_back(m, host_g, host_loss_pm);
+}
+
+extern "C" int zo_stream_begin(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t seed, float eps)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    if (m->cfg.residency != ZO_STREAMED) return fail(ZO_ESTATE, "not a streamed model");
+    ZO_TRY(check_batch(m, tokens, batch, seq));
+    if (!(eps > 0.0f)) return fail(ZO_EINVAL, "eps must be positive");
+    return stream_begin(m, tokens, batch, seq, seed, eps);
+}
+
+extern "C" int zo_stream_block(zo_model *m, int block, int phase_flags)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    if (m->cfg.residency != ZO_STREAMED) return fail(ZO_ESTATE, "not a streamed model");
+    if (block < 0 || block >= m->cfg.n_layers) return fail(ZO_EINVAL, "block %d outside [0, %d)", block, m->cfg.n_layers);
+    if (!phase_flags || (phase_flags & ~7)) return fail(ZO_EINVAL, "phase_flags %d invalid", phase_flags);
+    if (!m->step_open) return fail(ZO_ESTATE, "no streamed step is open (call zo_stream_begin)");
+    if (phase_flags & ZO_PHASE_PREFETCH) ZO_TRY(stream_prefetch(m, block));
+    if (phase_flags & ZO_PHASE_COMPUTE) {
+        if (block != m->next_block) return fail(ZO_ESTATE, "blocks must be computed in order: expected %d, got %d", m->next_block, block);
+        ZO_TRY(stream_compute(m, block, true));
+        m->next_block = block + 1;
+    }
+    if (phase_flags & ZO_PHASE_WRITEBACK) ZO_TRY(stream_writeback(m, block));
+    return ZO_OK;
+}
+
+extern "C" int zo_stream_end(zo_model *m, float lr, double *host_g, double *host_loss_pm)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    if (m->cfg.residency != ZO_STREAMED) return fail(ZO_ESTATE, "not a streamed model");
+    ZO_TRY(stream_end(m, lr));
+    return read_back(m, host_g, host_loss_pm);
+}
+
+extern "C" int zo_flush_pending(zo_model *m)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    if (m->cfg.residency != ZO_STREAMED || !m->pending) return ZO_OK;
+    if (m->step_open) return fail(ZO_ESTATE, "a streamed step is open");
+    const int lnf = 2 + kPerBlock * m->cfg.n_layers;
+    ZO_TRY(axpy_range(m, 0, 2, m->pending_seed, 0.0f, m->s_pending));
+    ZO_TRY(axpy_range(m, lnf, 2, m->pending_seed, 0.0f, m->s_pending));
+    ZO_TRY(stream_prefetch(m, 0));
+    for (int l = 0; l < m->cfg.n_layers; ++l) {
+        if (l + 1 < m->cfg.n_layers) ZO_TRY(stream_prefetch(m, l + 1));
+        ZO_TRY(stream_compute(m, l, false));
+        ZO_TRY(stream_writeback(m, l));
+    }
+    ZO_HIP(hipStreamSynchronize(m->download));
+    ZO_HIP(hipStreamSynchronize(m->compute));
+    m->pending = false;
+    return ZO_OK;
+}
+
+extern "C" int zo_device_flags(zo_model *m, uint32_t *host_flags)
+{
+    if (!m || !host_flags) return fail(ZO_EINVAL, "NULL argument");
+    ZO_HIP(hipMemcpyAsync(host_flags, m->flags, sizeof(uint32_t), hipMemcpyDeviceToHost, m->compute));
+    ZO_HIP(hipStreamSynchronize(m->compute));
+    return ZO_OK;
+}
+
+// ------------------------------------------------------------------ kernel-level entry points
+static int check_dtype(int dtype) { return dtype >= 0 && dtype <= 2 ? ZO_OK : fail(ZO_EINVAL, "dtype %d unknown", dtype); }
+
+extern "C" int zo_kernel_z(float *out, uint64_t n, uint64_t seed, uint32_t tensor_id, uint64_t first, void *stream)
+{
+    if (!out && n) return fail(ZO_EINVAL, "out is NULL");
+    ZO_HIP(launch_z(out, n, seed, tensor_id, first, (hipStream_t)stream));
+    return ZO_OK;
+}
+
+extern "C" int zo_kernel_normal_pairs(const uint32_t *words, float *z, uint64_t n_pairs, void *stream)
+{
+    if ((!words || !z) && n_pairs) return fail(ZO_EINVAL, "NULL argument");
+    ZO_HIP(launch_normal_pairs(words, z, n_pairs, (hipStream_t)stream));
+    return ZO_OK;
+}
+
+extern "C" int zo_kernel_axpy_z(const void *src, void *dst, int dtype, uint64_t n, uint64_t seed, uint32_t tensor_id, float scale,
+                                const float *dev_scale, void *stream)
+{
+    ZO_TRY(check_dtype(dtype));
+    if (n == 0) return ZO_OK;
+    if (!src || !dst) return fail(ZO_EINVAL, "NULL argument");
+    if ((uintptr_t)src % 16 || (uintptr_t)dst % 16) return fail(ZO_EINVAL, "buffers must be 16-byte aligned");
+    TensorDesc d{src, dst, n, 0, tensor_id, 0};
+    ZO_HIP(launch_axpy_single(d, dtype, seed, scale, dev_scale, (hipStream_t)stream));
+    return ZO_OK;
+}
+
+extern "C" int zo_kernel_stage_pm(const void *theta, void *w_plus, void *w_minus, int dtype, int rows, int cols, int transpose,
+                                  uint64_t seed, uint32_t tensor_id, float eps, void *stream)
+{
+    ZO_TRY(check_dtype(dtype));
+    if (!theta || !w_plus || !w_minus) return fail(ZO_EINVAL, "NULL argument");
+    if (rows < 1 || cols < 1) return fail(ZO_EINVAL, "bad shape %d x %d", rows, cols);
+    if (transpose && cols % 4) return fail(ZO_EINVAL, "transposed staging needs cols %% 4 == 0");
+    if ((uintptr_t)theta % 16 || (uintptr_t)w_plus % 16 || (uintptr_t)w_minus % 16) return fail(ZO_EINVAL, "buffers must be 16-byte aligned");
+    StageBatch b{};
+    stage_batch_add(b, theta, w_plus, w_minus, rows, cols, tensor_id, transpose != 0);
+    ZO_HIP(launch_stage(b, dtype, seed, eps, false, (hipStream_t)stream));
+    return ZO_OK;
+}
+
+extern "C" int zo_kernel_linear_pm(const void *x, const void *wt_plus, const void *wt_minus, const void *b_plus, const void *b_minus,
+                                   void *y, int dtype, int m_half, int n, int k, int epilogue, void *stream)
+{
+    ZO_TRY(check_dtype(dtype));
+    if (!x || !wt_plus || !wt_minus || !y) return fail(ZO_EINVAL, "NULL argument");
+    if (epilogue < 0 || epilogue > 3) return fail(ZO_EINVAL, "epilogue %d unknown", epilogue);
+    if (epilogue != 3 && (!b_plus || !b_minus)) return fail(ZO_EINVAL, "bias is NULL");
+    if (m_half < 1 || n < 1 || k < 1) return fail(ZO_EINVAL, "bad shape");
+    if (dtype != ZO_FP32 && (n % 8 || k % 8)) return fail(ZO_EINVAL, "n and k must be multiples of 8 for 2-byte types");
+    ZO_HIP(launch_linear(x, wt_plus, wt_minus, b_plus, b_minus, y, dtype, 2, m_half, n, k, epilogue, true, (hipStream_t)stream));
+    return ZO_OK;
+}
+
+extern "C" int zo_kernel_layernorm_pm(const void *resid, const void *g_plus, const void *g_minus, const void *b_plus, const void *b_minus,
+                                      void *y, int dtype, int m_half, int d, float ln_eps, void *stream)
+{
+    ZO_TRY(check_dtype(dtype));
+    if (!resid || !g_plus || !g_minus || !b_plus || !b_minus || !y) return fail(ZO_EINVAL, "NULL argument");
+    if (m_half < 1 || d < 1) return fail(ZO_EINVAL, "bad shape");
+    ZO_HIP(launch_layernorm(resid, g_plus, g_minus, b_plus, b_minus, y, dtype, 2, m_half, d, ln_eps, (hipStream_t)stream));
+    return ZO_OK;
+}
+
+extern "C" int zo_kernel_attention(const void *qkv, void *out, int dtype, int n_seq, int seq, int n_heads, int d_head, void *stream)
+{
+    ZO_TRY(check_dtype(dtype));
+    if (!qkv || !out) return fail(ZO_EINVAL, "NULL argument");
+    if (n_seq < 1 || seq < 1 || n_heads < 1 || d_head < 1 || d_head > 128) return fail(ZO_EINVAL, "bad shape");
+    if (dtype != ZO_FP32 && d_head % 8) return fail(ZO_EINVAL, "d_head must be a multiple of 8 for 2-byte types");
+    ZO_HIP(launch_attention(qkv, out, dtype, n_seq, seq, n_heads, d_head, true, (hipStream_t)stream));
+    return ZO_OK;
+}
+
+static int lmhead_rows(int m_half) { return m_half < 2048 ? m_half : 2048; }
+
+extern "C" size_t zo_kernel_lmhead_scratch_bytes(int dtype, int m_half, int vocab)
+{
+    if (dtype < 0 || dtype > 2 || m_half < 1 || vocab < 1) return 0;
+    return (size_t)lmhead_rows(m_half) * vocab * acc_bytes(dtype);
+}
+
+extern "C" int zo_kernel_lmhead_ce(const void *x, const void *e_plus, const void *e_minus, const int32_t *target, double *row_loss,
+                                   void *scratch, int dtype, int m_half, int d, int vocab, void *stream)
+{
+    ZO_TRY(check_dtype(dtype));
+    if (!x || !e_plus || !e_minus || !target || !row_loss || !scratch) return fail(ZO_EINVAL, "NULL argument");
+    if (m_half < 1 || d < 1 || vocab < 2) return fail(ZO_EINVAL, "bad shape");
+    if (dtype != ZO_FP32 && (d % 8 || vocab % 8)) return fail(ZO_EINVAL, "d and vocab must be multiples of 8 for 2-byte types");
+    return lmhead_ce((hipStream_t)stream, x, e_plus, e_minus, target, row_loss, scratch, lmhead_rows(m_half), dtype, 2, m_half, d, vocab, true);
+}

@@ -1,0 +1,315 @@
+// Perturb / update streams (DistZO2 App. A, Alg. 1: PerturbParameters and UpdateParameters;
+// Eq. 2) and the out-of-place staging of W+- = rn(theta +- eps z) (PertP workflow, Step 2).
+//
+// All of them are one pass over the parameters with z regenerated in registers from its
+// counter: 16-byte coalesced loads and stores, four independent Philox blocks per thread for
+// instruction-level parallelism, no LDS except for the transposing stage.
+#include "zo_kernels.h"
+#include "zo_rng.hip.h"
+#include "zo_types.hip.h"
+
+namespace zo {
+
+// ------------------------------------------------------------------ z only (verification)
+__global__ __launch_bounds__(256) void z_kernel(float *out, uint64_t n, uint64_t seed, uint32_t tid, uint64_t first)
+{
+    // one Philox block per thread; blocks first/4 .. (first+n-1)/4
+    const uint64_t j = first / 4 + (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (4 * j >= first + n) return;
+    float z[4];
+    normal4(philox_block(seed, tid, j), z);
+#pragma unroll
+    for (int l = 0; l < 4; ++l) {
+        const uint64_t i = 4 * j + l;
+        if (i >= first && i < first + n) out[i - first] = z[l];
+    }
+}
+
+__global__ __launch_bounds__(256) void normal_pairs_kernel(const uint32_t *words, float *z, uint64_t n_pairs)
+{
+    const uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n_pairs) return;
+    float a, b;
+    normal_pair(words[2 * p], words[2 * p + 1], a, b);
+    z[2 * p] = a;
+    z[2 * p + 1] = b;
+}
+
+// ------------------------------------------------------------------ in-place axpy with z
+template <int DT> struct Vec16;   // 16 bytes of storage elements
+template <> struct Vec16<kFP32> { static constexpr int N = 4; };
+template <> struct Vec16<kBF16> { static constexpr int N = 8; };
+template <> struct Vec16<kFP16> { static constexpr int N = 8; };
+
+template <int DT> __device__ __forceinline__ void unpack16(const uint4 &v, float *f)
+{
+    if constexpr (DT == kFP32) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    } else {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = Prec<DT>::w2f((uint16_t)(w[i] & 0xffffu));
+            f[2 * i + 1] = Prec<DT>::w2f((uint16_t)(w[i] >> 16));
+        }
+    }
+}
+template <int DT> __device__ __forceinline__ uint4 pack16(const float *f)
+{
+    if constexpr (DT == kFP32) {
+        return uint4{__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3])};
+    } else {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)Prec<DT>::f2w(f[2 * i]) | ((uint32_t)Prec<DT>::f2w(f[2 * i + 1]) << 16);
+        return uint4{w[0], w[1], w[2], w[3]};
+    }
+}
+
+// One workgroup = one chunk of kAxpyChunk elements of one tensor.
+template <int DT>
+__global__ __launch_bounds__(256) void axpy_z_kernel(const TensorDesc *__restrict__ descs, int n_desc, TensorDesc single,
+                                                     uint64_t chunk_offset, uint64_t seed, float scale,
+                                                     const float *__restrict__ dev_scale)
+{
+    using W = typename Prec<DT>::W;
+    constexpr int VN = Vec16<DT>::N;
+    TensorDesc d;
+    const uint64_t chunk = (uint64_t)blockIdx.x + chunk_offset;
+    if (descs) {
+        // last descriptor whose first_chunk <= chunk
+        int lo = 0, hi = n_desc - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (descs[mid].first_chunk <= chunk) lo = mid; else hi = mid - 1;
+        }
+        d = descs[lo];
+    } else {
+        d = single;
+    }
+    const float sc = dev_scale ? *dev_scale : scale;
+    const uint64_t base = (chunk - d.first_chunk) * kAxpyChunk;
+    const W *__restrict__ src = (const W *)d.src;
+    W *__restrict__ dst = (W *)d.dst;
+    constexpr int kIter = kAxpyChunk / (256 * VN);
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+        const uint64_t i0 = base + (uint64_t)(it * 256 + threadIdx.x) * VN;
+        if (i0 >= d.numel) break;
+        float z[VN];
+#pragma unroll
+        for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b);
+        if (i0 + VN <= d.numel) {
+            float th[VN];
+            unpack16<DT>(*(const uint4 *)(src + i0), th);
+#pragma unroll
+            for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
+            *(uint4 *)(dst + i0) = pack16<DT>(th);
+        } else {
+            for (int e = 0; e < VN && i0 + e < d.numel; ++e)
+                dst[i0 + e] = Prec<DT>::f2w(__builtin_fmaf(sc, z[e], Prec<DT>::w2f(src[i0 + e])));
+        }
+    }
+}
+
+// ------------------------------------------------------------------ staging W+ / W-
+// Flat tiles copy kStageFlatTile consecutive elements; transposing tiles move a 64 x 64 patch
+// of a [rows, cols] matrix through LDS so that both the read (along cols) and the write
+// (along rows of the transposed result) are coalesced.
+template <int DT, bool SINGLE>
+__global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t seed, float eps)
+{
+    using W = typename Prec<DT>::W;
+    constexpr int VN = Vec16<DT>::N;
+    int di = 0;
+    for (int i = 1; i < batch.n; ++i)
+        if (batch.d[i].first_tile <= blockIdx.x) di = i;
+    const StageDesc &d = batch.d[di];
+    const uint32_t tile = blockIdx.x - d.first_tile;
+    const W *__restrict__ src = (const W *)d.src;
+    W *__restrict__ dp = (W *)d.dst_plus;
+    W *__restrict__ dm = (W *)d.dst_minus;
+    const uint64_t numel = (uint64_t)d.rows * d.cols;
+
+    if (!d.transpose) {
+        constexpr int kIter = kStageFlatTile / (256 * VN);
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            const uint64_t i0 = (uint64_t)tile * kStageFlatTile + (uint64_t)(it * 256 + threadIdx.x) * VN;
+            if (i0 >= numel) break;
+            float z[VN];
+            if constexpr (!SINGLE) {
+#pragma unroll
+                for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b);
+            }
+            if (i0 + VN <= numel) {
+                const uint4 raw = *(const uint4 *)(src + i0);
+                if constexpr (SINGLE) {
+                    *(uint4 *)(dp + i0) = raw;
+                } else {
+                    float th[VN], a[VN], b[VN];
+                    unpack16<DT>(raw, th);
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) {
+                        a[e] = __builtin_fmaf(eps, z[e], th[e]);
+                        b[e] = __builtin_fmaf(-eps, z[e], th[e]);
+                    }
+                    *(uint4 *)(dp + i0) = pack16<DT>(a);
+                    *(uint4 *)(dm + i0) = pack16<DT>(b);
+                }
+            } else {
+                for (int e = 0; e < VN && i0 + e < numel; ++e) {
+                    const float th = Prec<DT>::w2f(src[i0 + e]);
+                    if constexpr (SINGLE) {
+                        dp[i0 + e] = src[i0 + e];
+                    } else {
+                        dp[i0 + e] = Prec<DT>::f2w(__builtin_fmaf(eps, z[e], th));
+                        dm[i0 + e] = Prec<DT>::f2w(__builtin_fmaf(-eps, z[e], th));
+                    }
+                }
+            }
+        }
+        return;
+    }
+
+    // transposing tile: rows r0.., cols c0..  (cols % 4 == 0 is guaranteed by the caller)
+    constexpr int T = (int)kStageTile;
+    constexpr int LD = T + 16 / (int)sizeof(W);     // padded row, keeps 16-byte alignment
+    __shared__ __attribute__((aligned(16))) W sp[T * LD];
+    __shared__ __attribute__((aligned(16))) W sm[SINGLE ? 1 : T * LD];
+    const uint32_t r0 = (tile / d.tiles_c) * T, c0 = (tile % d.tiles_c) * T;
+    // read: thread -> (row = tid/16 + 16*it, four columns 4*(tid%16)..+3): one Philox block each
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const uint32_t lr = threadIdx.x / 16 + 16 * it, lc = 4 * (threadIdx.x % 16);
+        const uint32_t r = r0 + lr, c = c0 + lc;
+        if (r < d.rows && c < d.cols) {
+            const uint64_t i0 = (uint64_t)r * d.cols + c;
+            W raw[4];
+            if constexpr (sizeof(W) == 2) *(uint2 *)raw = *(const uint2 *)(src + i0);
+            else *(uint4 *)raw = *(const uint4 *)(src + i0);
+            if constexpr (SINGLE) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sp[(lc + e) * LD + lr] = raw[e];
+            } else {
+                float z[4];
+                normal4(philox_block(seed, d.tid, i0 / 4), z);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float th = Prec<DT>::w2f(raw[e]);
+                    sp[(lc + e) * LD + lr] = Prec<DT>::f2w(__builtin_fmaf(eps, z[e], th));
+                    sm[(lc + e) * LD + lr] = Prec<DT>::f2w(__builtin_fmaf(-eps, z[e], th));
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // write: output row = source column c0 + tid/4, 16 consecutive source rows starting at r0 + 16*(tid%4)
+    const uint32_t oc = threadIdx.x / 4, seg = 16 * (threadIdx.x % 4);
+    if (c0 + oc < d.cols) {
+        const uint64_t o0 = (uint64_t)(c0 + oc) * d.rows + r0 + seg;
+        const bool full = (r0 + seg + 16 <= d.rows) && ((d.rows * sizeof(W)) % 16 == 0);
+        if (full) {
+            constexpr int NV = 16 * (int)sizeof(W) / 16;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                ((uint4 *)(dp + o0))[v] = ((const uint4 *)(sp + oc * LD + seg))[v];
+                if constexpr (!SINGLE) ((uint4 *)(dm + o0))[v] = ((const uint4 *)(sm + oc * LD + seg))[v];
+            }
+        } else {
+            for (uint32_t e = 0; e < 16 && r0 + seg + e < d.rows; ++e) {
+                dp[o0 + e] = sp[oc * LD + seg + e];
+                if constexpr (!SINGLE) dm[o0 + e] = sm[oc * LD + seg + e];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ launchers
+hipError_t launch_z(float *out, uint64_t n, uint64_t seed, uint32_t tid, uint64_t first, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    const uint64_t blocks = (first + n - 1) / 4 - first / 4 + 1;
+    z_kernel<<<dim3((unsigned)((blocks + 255) / 256)), dim3(256), 0, s>>>(out, n, seed, tid, first);
+    return hipGetLastError();
+}
+
+hipError_t launch_normal_pairs(const uint32_t *words, float *z, uint64_t n_pairs, hipStream_t s)
+{
+    if (n_pairs == 0) return hipSuccess;
+    normal_pairs_kernel<<<dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, s>>>(words, z, n_pairs);
+    return hipGetLastError();
+}
+
+template <int DT>
+static hipError_t axpy_launch_t(const TensorDesc *descs, int n_desc, const TensorDesc &single, uint64_t chunk_offset,
+                                uint64_t chunks, uint64_t seed, float scale, const float *dev_scale, hipStream_t s)
+{
+    if (chunks == 0) return hipSuccess;
+    if (chunks > 0x7fffffffull) return hipErrorInvalidValue;
+    axpy_z_kernel<DT><<<dim3((unsigned)chunks), dim3(256), 0, s>>>(descs, n_desc, single, chunk_offset, seed, scale,
+                                                                  dev_scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_axpy_multi(const TensorDesc *dev_descs, int n_desc, uint64_t chunk_offset, uint64_t total_chunks,
+                             int dtype, uint64_t seed, float scale, const float *dev_scale, hipStream_t s)
+{
+    TensorDesc none{};
+    switch (dtype) {
+    case kFP32: return axpy_launch_t<kFP32>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, s);
+    case kBF16: return axpy_launch_t<kBF16>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, s);
+    case kFP16: return axpy_launch_t<kFP16>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_axpy_single(const TensorDesc &d, int dtype, uint64_t seed, float scale, const float *dev_scale,
+                              hipStream_t s)
+{
+    const uint64_t chunks = (d.numel + kAxpyChunk - 1) / kAxpyChunk;
+    TensorDesc one = d;
+    one.first_chunk = 0;
+    switch (dtype) {
+    case kFP32: return axpy_launch_t<kFP32>(nullptr, 0, one, 0, chunks, seed, scale, dev_scale, s);
+    case kBF16: return axpy_launch_t<kBF16>(nullptr, 0, one, 0, chunks, seed, scale, dev_scale, s);
+    case kFP16: return axpy_launch_t<kFP16>(nullptr, 0, one, 0, chunks, seed, scale, dev_scale, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+void stage_batch_add(StageBatch &b, const void *src, void *dp, void *dm, uint32_t rows, uint32_t cols, uint32_t tid,
+                     bool transpose)
+{
+    StageDesc &d = b.d[b.n++];
+    d.src = src; d.dst_plus = dp; d.dst_minus = dm; d.rows = rows; d.cols = cols; d.tid = tid;
+    d.transpose = transpose ? 1u : 0u;
+    d.first_tile = b.total_tiles;
+    if (transpose) {
+        d.tiles_c = (cols + kStageTile - 1) / kStageTile;
+        b.total_tiles += d.tiles_c * ((rows + kStageTile - 1) / kStageTile);
+    } else {
+        d.tiles_c = 0;
+        b.total_tiles += (uint32_t)(((uint64_t)rows * cols + kStageFlatTile - 1) / kStageFlatTile);
+    }
+}
+
+hipError_t launch_stage(const StageBatch &b, int dtype, uint64_t seed, float eps, bool single_copy, hipStream_t s)
+{
+    if (b.total_tiles == 0) return hipSuccess;
+    const dim3 grid(b.total_tiles), block(256);
+#define ZO_STAGE(DT)                                                                      \
+    if (single_copy) stage_kernel<DT, true><<<grid, block, 0, s>>>(b, seed, eps);          \
+    else stage_kernel<DT, false><<<grid, block, 0, s>>>(b, seed, eps);                     \
+    return hipGetLastError();
+    switch (dtype) {
+    case kFP32: ZO_STAGE(kFP32)
+    case kBF16: ZO_STAGE(kBF16)
+    case kFP16: ZO_STAGE(kFP16)
+    }
+#undef ZO_STAGE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace zo

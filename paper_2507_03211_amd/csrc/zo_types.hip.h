@@ -1,0 +1,101 @@
+// Storage / activation types of the three precisions and small device helpers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace zo {
+
+constexpr int kFP32 = 0, kBF16 = 1, kFP16 = 2;
+
+// ---- scalar conversions (round to nearest even, as the perturbation is specified) ----
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t x = __float_as_uint(f);
+    if ((x & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x >> 16) | 0x0040u);
+    x += 0x7fffu + ((x >> 16) & 1u);
+    return (uint16_t)(x >> 16);
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t h)
+{
+    _Float16 v;
+    __builtin_memcpy(&v, &h, 2);
+    return (float)v;
+}
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
+{
+    _Float16 v = (_Float16)f;   // v_cvt_f16_f32: nearest even, subnormals kept
+    uint16_t h;
+    __builtin_memcpy(&h, &v, 2);
+    return h;
+}
+
+// Per-precision types.  W: parameter storage, A: activations between kernels, R: residual
+// stream, Acc: accumulator / statistics.  fp32 parameters run with fp64 activations: g is a
+// difference of two nearly equal losses, and fp32 activation rounding alone would eat the
+// tolerance asked of that configuration.
+template <int DT> struct Prec;
+template <> struct Prec<kFP32> {
+    using W = float; using A = double; using R = double; using Acc = double;
+    static __device__ __forceinline__ float w2f(W v) { return v; }
+    static __device__ __forceinline__ W f2w(float v) { return v; }
+    static __device__ __forceinline__ Acc a2acc(A v) { return v; }
+    static __device__ __forceinline__ A acc2a(Acc v) { return v; }
+};
+template <> struct Prec<kBF16> {
+    using W = uint16_t; using A = uint16_t; using R = float; using Acc = float;
+    static __device__ __forceinline__ float w2f(W v) { return bf16_bits_to_f32(v); }
+    static __device__ __forceinline__ W f2w(float v) { return f32_to_bf16_bits(v); }
+    static __device__ __forceinline__ Acc a2acc(A v) { return bf16_bits_to_f32(v); }
+    static __device__ __forceinline__ A acc2a(Acc v) { return f32_to_bf16_bits(v); }
+};
+template <> struct Prec<kFP16> {
+    using W = uint16_t; using A = uint16_t; using R = float; using Acc = float;
+    static __device__ __forceinline__ float w2f(W v) { return f16_bits_to_f32(v); }
+    static __device__ __forceinline__ W f2w(float v) { return f32_to_f16_bits(v); }
+    static __device__ __forceinline__ Acc a2acc(A v) { return f16_bits_to_f32(v); }
+    static __device__ __forceinline__ A acc2a(Acc v) { return f32_to_f16_bits(v); }
+};
+
+inline size_t elem_bytes(int dtype) { return dtype == kFP32 ? 4 : 2; }
+inline size_t act_bytes(int dtype) { return dtype == kFP32 ? 8 : 2; }
+inline size_t resid_bytes(int dtype) { return dtype == kFP32 ? 8 : 4; }
+inline size_t acc_bytes(int dtype) { return dtype == kFP32 ? 8 : 4; }
+
+// ---- block-wide reductions (blockDim.x multiple of 64, <= 1024) ----
+template <typename T> __device__ __forceinline__ T wave_sum(T v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+template <typename T> __device__ __forceinline__ T wave_max(T v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { T t = __shfl_xor(v, o, 64); v = t > v ? t : v; }
+    return v;
+}
+template <typename T> __device__ __forceinline__ T block_sum(T v, T *smem /* >= 16 */)
+{
+    v = wave_sum(v);
+    const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) smem[w] = v;
+    __syncthreads();
+    T t = 0;
+    for (int i = 0; i < nw; ++i) t += smem[i];
+    return t;
+}
+template <typename T> __device__ __forceinline__ T block_max(T v, T *smem)
+{
+    v = wave_max(v);
+    const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) smem[w] = v;
+    __syncthreads();
+    T t = smem[0];
+    for (int i = 1; i < nw; ++i) t = smem[i] > t ? smem[i] : t;
+    return t;
+}
+
+}  // namespace zo
