@@ -220,8 +220,10 @@ int stage_globals(zo_model *m, int seq, uint64_t seed, float eps)
     return ZO_OK;
 }
 
-// Stage one block from `src_base` (16 tensors in canonical order) into the per-sign scratch.
-int stage_block(zo_model *m, int layer, const char *src_base, uint64_t seed, float eps, bool single)
+// Stage one block into the per-sign scratch.  `slot_base` == nullptr: the block's 16 tensors are read
+// where the caller keeps them (resident model, separately allocated); otherwise from a device copy of
+// the block laid out contiguously in canonical order (streamed model).
+int stage_block(zo_model *m, int layer, const char *slot_base, uint64_t seed, float eps, bool single)
 {
     const zo_config &c = m->cfg;
     const BlockLayout &L = m->lay;
@@ -230,7 +232,8 @@ int stage_block(zo_model *m, int layer, const char *src_base, uint64_t seed, flo
     const int t0 = 2 + kPerBlock * layer;
     StageBatch b{};
     auto add = [&](int k, size_t dst_off, bool tr) {
-        stage_batch_add(b, src_base + L.src_off[k] * e, sp + dst_off * e, sm + dst_off * e, L.rows[k], L.cols[k], t0 + k, tr);
+        const void *src = slot_base ? (const void *)(slot_base + L.src_off[k] * e) : (const void *)m->tptr[t0 + k];
+        stage_batch_add(b, src, sp + dst_off * e, sm + dst_off * e, L.rows[k], L.cols[k], t0 + k, tr);
     };
     add(T_LN1G, L.st_ln1g, false); add(T_LN1B, L.st_ln1b, false);
     add(T_WQ, L.st_wqkv, true); add(T_WK, L.st_wqkv + D * D, true); add(T_WV, L.st_wqkv + 2 * D * D, true);
@@ -322,7 +325,7 @@ int forward_fused_resident(zo_model *m, const int32_t *tokens, int batch, int se
     const char *ep = m->ws + m->wsp.e_pm[0], *em = m->ws + m->wsp.e_pm[1];
     ZO_TRY(embed(m, tokens, 2, batch, seq, ep, em, m->ws + m->wsp.pos_pm[0], m->ws + m->wsp.pos_pm[1]));
     for (int l = 0; l < c.n_layers; ++l) {
-        ZO_TRY(stage_block(m, l, (const char *)m->tptr[2 + kPerBlock * l], seed, eps, false));
+        ZO_TRY(stage_block(m, l, nullptr, seed, eps, false));
         ZO_TRY(block_forward(m, 2, batch, seq));
     }
     return head_and_loss(m, 2, batch, seq, ep, em, m->ws + m->wsp.lnf_pm[0], m->ws + m->wsp.lnf_pm[1], m->loss_pm);
@@ -341,7 +344,7 @@ int forward_single(zo_model *m, const int32_t *tokens, int batch, int seq, int s
     ZO_HIP(launch_stage(b, c.dtype, 0, 0.0f, true, m->compute));
     ZO_TRY(embed(m, tokens, 1, batch, seq, m->tptr[0], m->tptr[0], m->tptr[1], m->tptr[1]));
     for (int l = 0; l < c.n_layers; ++l) {
-        ZO_TRY(stage_block(m, l, (const char *)m->tptr[2 + kPerBlock * l], 0, 0.0f, true));
+        ZO_TRY(stage_block(m, l, nullptr, 0, 0.0f, true));
         ZO_TRY(block_forward(m, 1, batch, seq));
     }
     return head_and_loss(m, 1, batch, seq, m->tptr[0], m->tptr[0], m->ws + m->wsp.lnf_pm[0], m->ws + m->wsp.lnf_pm[0],

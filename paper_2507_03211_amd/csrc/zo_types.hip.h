@@ -24,10 +24,13 @@ __device__ __forceinline__ float f16_bits_to_f32(uint16_t h)
 }
 __device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
 {
-    _Float16 v = (_Float16)f;   // v_cvt_f16_f32: nearest even, subnormals kept
-    uint16_t h;
-    __builtin_memcpy(&h, &v, 2);
-    return h;
+    // Nearest even, subnormals kept.  Written as an explicit instruction so that the compiler cannot
+    // fold a preceding fp32 fma and this conversion into v_fma_mixlo_f16, which rounds the exact fma
+    // result once, straight to fp16: the perturbation is specified as an fp32 fma (one rounding)
+    // followed by the rounding into the storage type (a second one), and the two differ in rare ties.
+    uint32_t h;
+    asm("v_cvt_f16_f32 %0, %1" : "=v"(h) : "v"(f));
+    return (uint16_t)(h & 0xffffu);
 }
 
 // Per-precision types.  W: parameter storage, A: activations between kernels, R: residual
