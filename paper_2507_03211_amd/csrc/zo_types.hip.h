@@ -24,13 +24,20 @@ __device__ __forceinline__ float f16_bits_to_f32(uint16_t h)
 }
 __device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
 {
-    // Nearest even, subnormals kept.  Written as an explicit instruction so that the compiler cannot
-    // fold a preceding fp32 fma and this conversion into v_fma_mixlo_f16, which rounds the exact fma
-    // result once, straight to fp16: the perturbation is specified as an fp32 fma (one rounding)
-    // followed by the rounding into the storage type (a second one), and the two differ in rare ties.
-    uint32_t h;
-    asm("v_cvt_f16_f32 %0, %1" : "=v"(h) : "v"(f));
-    return (uint16_t)(h & 0xffffu);
+    _Float16 v = (_Float16)f;   // v_cvt_f16_f32: nearest even, subnormals kept
+    uint16_t h;
+    __builtin_memcpy(&h, &v, 2);
+    return h;
+}
+// Same conversion for parameter storage.  The perturbation is specified as an fp32 fma (one rounding)
+// followed by the rounding into the storage type (a second one).  Left alone, the compiler folds the
+// two into v_fma_mixlo_f16, which rounds the exact fma result once, straight to fp16, and differs in
+// rare ties.  The empty asm makes the fp32 value opaque so the fold cannot happen; it emits no
+// instruction, so the compiler still sees (and pads) every hazard around the real ones.
+__device__ __forceinline__ uint16_t f32_to_f16_bits_unfused(float f)
+{
+    asm volatile("" : "+v"(f));
+    return f32_to_f16_bits(f);
 }
 
 // Per-precision types.  W: parameter storage, A: activations between kernels, R: residual
@@ -55,7 +62,7 @@ template <> struct Prec<kBF16> {
 template <> struct Prec<kFP16> {
     using W = uint16_t; using A = uint16_t; using R = float; using Acc = float;
     static __device__ __forceinline__ float w2f(W v) { return f16_bits_to_f32(v); }
-    static __device__ __forceinline__ W f2w(float v) { return f32_to_f16_bits(v); }
+    static __device__ __forceinline__ W f2w(float v) { return f32_to_f16_bits_unfused(v); }
     static __device__ __forceinline__ Acc a2acc(A v) { return f16_bits_to_f32(v); }
     static __device__ __forceinline__ A acc2a(Acc v) { return f32_to_f16_bits(v); }
 };

@@ -87,7 +87,8 @@ def test_linear_pm(dtype, m_half, n, k, epi):
 
 
 @pytest.mark.parametrize("dtype", [zi.FP32, zi.BF16, zi.FP16])
-@pytest.mark.parametrize("n_seq,seq,heads,dh", [(2, 32, 4, 16), (3, 70, 2, 64), (1, 200, 1, 128), (2, 130, 3, 32)])
+@pytest.mark.parametrize("n_seq,seq,heads,dh", [(2, 32, 4, 16), (3, 70, 2, 64), (1, 200, 1, 128), (2, 130, 3, 32),
+                                                (2, 300, 2, 64), (1, 257, 2, 128), (2, 512, 3, 64), (1, 1, 1, 64)])
 def test_attention(dtype, n_seq, seq, heads, dh):
     rng = np.random.Generator(np.random.PCG64(seq * 3 + dh))
     d = heads * dh
