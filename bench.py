@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Throughput of the ZO-SGD step (dual +-eps z forward + update) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config opt-13b]
+
+A step is one zo_step through the C-ABI: stage W+- = rn(theta +- eps z) block by block, the
+sign-batched forward of both perturbed models, g, and the regenerated-z update of every
+parameter.  Inputs (weights ~ 0.02 N(0,1) drawn on the device by torch, uniform random
+tokens) are resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f64": 78.6}
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="opt-13b", help="tiny | opt-125m | opt-1.3b | opt-13b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def device_weights(torch, shapes, dtype_code, dev, seed=0):
+    tdt = {0: torch.float32, 1: torch.bfloat16, 2: torch.float16}[dtype_code]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    out = []
+    for name, shape in shapes:
+        leaf = name.split(".")[-1]
+        if len(shape) == 2:
+            t = torch.empty(shape, dtype=tdt, device=dev).normal_(0.0, 0.02, generator=gen)
+        elif leaf.endswith("_g"):
+            t = torch.ones(shape, dtype=tdt, device=dev)
+        else:
+            t = torch.zeros(shape, dtype=tdt, device=dev)
+        out.append(t)
+    return out
+
+
+def _cores():
+    n = os.cpu_count() or 1
+    try:
+        n = min(n, int(os.environ.get("OMP_NUM_THREADS", n)))
+    except ValueError:
+        pass
+    return n
+
+
+def cpu_baseline(cfgd, name):
+    """The oracle, as it stands, on a bounded sample of the same workload: one decoder block at the
+    real width (both signs: z, W+-, forward; then its update) plus embeddings / LM head / loss, on a
+    reduced token count.  Per-parameter cost is extrapolated to all blocks, per-token cost to the
+    full batch."""
+    import numpy as np
+    import zo_inputs as zi
+    from oracle import zo_oracle as zo
+    d, f, V, L = cfgd["d_model"], cfgd["d_ffn"], cfgd["vocab"], cfgd["n_layers"]
+    dt = cfgd["dtype"]
+    full_tokens = cfgd["batch"] * cfgd["seq"]
+    if name == "tiny":
+        ocfg = zo.Config(L, d, cfgd["n_heads"], f, V, cfgd["max_pos"], dt)
+        theta = zi.make_weights(ocfg.shapes(), dt, seed=0)
+        tok = zi.make_tokens(cfgd["batch"], cfgd["seq"], V)
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < 5.0:
+            zo.zo_step_fused(ocfg, theta, tok, n, cfgd["eps"], cfgd["lr"])
+            n += 1
+        dtm = (time.perf_counter() - t0) / n
+        return {"value": full_tokens / dtm, "unit": "tokens/s", "cores": _cores(), "kind": "oracle",
+                "sample": "%d whole steps of the same workload" % n}
+    s_seq = min(cfgd["seq"], 64 if d >= 4096 else 128)
+    s_vocab = min(V, 8192)
+    ocfg = zo.Config(1, d, cfgd["n_heads"], f, s_vocab, s_seq, dt)
+    theta = zi.make_weights(ocfg.shapes(), dt, seed=0)
+    tok = zi.make_tokens(1, s_seq, s_vocab)
+    blk = ocfg.block_ids(0)
+    eps = cfgd["eps"]
+    t0 = time.perf_counter()
+    wp = [zo.widen(zo.axpy_z(theta[i], dt, 0, i, eps), dt) for i in blk]
+    wm = [zo.widen(zo.axpy_z(theta[i], dt, 0, i, -np.float32(eps)), dt) for i in blk]
+    t_stage = time.perf_counter() - t0
+    h = zo.embed(tok, zo.widen(theta[0], dt), zo.widen(theta[1], dt))
+    t0 = time.perf_counter()
+    hp = zo.block_forward(h, dict(zip(zo.BLOCK_TENSORS, wp)), ocfg.n_heads, ocfg.ln_eps)
+    hm = zo.block_forward(h, dict(zip(zo.BLOCK_TENSORS, wm)), ocfg.n_heads, ocfg.ln_eps)
+    t_fwd = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for i in blk:
+        zo.axpy_z(theta[i], dt, 0, i, -1e-7, out=theta[i])
+    t_upd = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    e64 = zo.widen(theta[0], dt)
+    for hh in (hp, hm):
+        zo.next_token_loss(zo.head_logits(hh, zo.widen(theta[2 + 16], dt), zo.widen(theta[3 + 16], dt), e64, ocfg.ln_eps), tok)
+    t_head = time.perf_counter() - t0
+    per_block_params = sum(theta[i].size for i in blk)
+    embed_params = V * d + cfgd["max_pos"] * d
+    fixed = (t_stage + t_upd) * (L + embed_params / per_block_params)
+    per_token = (L * t_fwd + t_head * (V / s_vocab)) / s_seq
+    step_s = fixed + per_token * full_tokens
+    return {"value": full_tokens / step_s, "unit": "tokens/s", "cores": _cores(), "kind": "oracle",
+            "sample": "1 of %d blocks at real width with 1 x %d tokens and a %d-row LM head, timed %.1f s; per-parameter cost "
+                      "(z, W+-, update) scaled to all parameters, per-token cost to %d tokens (extrapolated)"
+                      % (L, s_seq, s_vocab, t_stage + t_fwd + t_upd + t_head, full_tokens)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one MI355X runs the whole ZO-SGD step); run with --gpus 1. "
+              "No figure for %d GPUs exists." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2507_03211_amd as zo_amd
+    import zo_inputs as zi
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    c = zi.CONFIGS[args.config]
+    dev = "cuda:0"
+    shapes = zi.tensor_shapes(c["n_layers"], c["d_model"], c["d_ffn"], c["vocab"], c["max_pos"])
+    tensors = device_weights(torch, shapes, c["dtype"], dev)
+    tokens = torch.randint(0, c["vocab"], (c["batch"], c["seq"]), dtype=torch.int32, device=dev,
+                           generator=torch.Generator(device=dev).manual_seed(1))
+    cfg = zo_amd.make_config(c["n_layers"], c["d_model"], c["n_heads"], c["d_ffn"], c["vocab"], c["max_pos"], c["dtype"])
+    nbytes = zo_amd.zo_workspace_bytes(cfg, c["batch"], c["seq"])
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream(device=dev)
+    torch.cuda.synchronize()
+    h = zo_amd.zo_init_model(cfg, tensors, ws, nbytes, c["batch"], c["seq"], stream, None)
+
+    def step(i):
+        zo_amd.zo_step(h, tokens, c["batch"], c["seq"], i, c["eps"], c["lr"], zo_amd.ZO_MODE_FUSED, want_host=False)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    launches_per_step = 16 * c["n_layers"] + 64 + 4 * ((2 * c["batch"] * c["seq"]) // 2048 + 2)
+    zo_amd.zo_profile_begin(h, launches_per_step * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = zo_amd.zo_profile_end(h)
+    lp, lm, g = zo_amd.zo_step(h, tokens, c["batch"], c["seq"], 10**6, c["eps"], c["lr"])
+    flags = zo_amd.zo_device_flags(h)
+    zo_amd.zo_free(h)
+
+    tokens_per_step = c["batch"] * c["seq"]
+    dname = {0: "f64", 1: "bf16", 2: "f16"}[c["dtype"]]
+    kernels = {}
+    for name, (ms, n, work) in prof.items():
+        if n == 0:
+            continue
+        rate = work / (ms * 1e-3) if ms > 0 else 0.0
+        is_flop = name in ("linear", "attention")
+        kernels[name] = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
+                         "achieved": rate / (1e12 if is_flop else 1e9), "unit": "TFLOP/s" if is_flop else "GB/s"}
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    dom_ms, dom_n, dom_work = prof[dom]
+    if dom in ("linear", "attention"):
+        peak = PEAK_TFLOPS[dname]
+        ach = dom_work / (dom_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma" if dname != "f64" else "alu", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak}
+    else:
+        ach = dom_work / (dom_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
+    roof["kernel"] = dom
+    roof["avg_launch_ms"] = dom_ms / max(dom_n, 1)
+    roof["work_per_launch"] = dom_work / max(dom_n, 1)
+    roof["traffic"] = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            roof["traffic"] = json.load(open(tpath)).get(args.config, {}).get(dom)
+        except Exception:
+            roof["traffic"] = None
+
+    out = {
+        "metric": "ZO-SGD tokens/s on 1 MI355X (dual +-eps z forward + update)",
+        "value": tokens_per_step * args.steps / dt,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dname, "data": "synthetic",
+        "config": {"workload": args.config, "n_layers": c["n_layers"], "d_model": c["d_model"], "n_heads": c["n_heads"],
+                   "d_ffn": c["d_ffn"], "vocab": c["vocab"], "batch": c["batch"], "seq_len": c["seq"], "eps": c["eps"],
+                   "lr": c["lr"], "mode": "fused", "residency": "hbm"},
+        "roofline": roof,
+        "kernels": kernels,
+        "last_step": {"l_plus": lp, "l_minus": lm, "g": g, "device_flags": flags},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(c, args.config)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

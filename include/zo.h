@@ -153,6 +153,17 @@ int zo_flush_pending(zo_model *m);
  * update, bit 1 = token id out of range.  Synchronises the compute stream. */
 int zo_device_flags(zo_model *m, uint32_t *host_flags);
 
+/* Per-launch timing of the model's kernels with HIP events on the compute stream, by class.
+ * Between begin and end every kernel the model launches is bracketed by two events (up to
+ * max_launches launches; later ones are not recorded).  zo_profile_end synchronises the compute
+ * stream and fills three host arrays of ZO_K_CLASSES entries: summed kernel milliseconds, number
+ * of launches, and summed algorithmic work (FLOP for LINEAR and ATTENTION -- 2 m n k, causal half
+ * for attention -- bytes that must cross HBM for the others). */
+enum { ZO_K_LINEAR = 0, ZO_K_ATTENTION = 1, ZO_K_STAGE = 2, ZO_K_UPDATE = 3, ZO_K_NORM = 4, ZO_K_CE = 5, ZO_K_OTHER = 6,
+       ZO_K_CLASSES = 7 };
+int zo_profile_begin(zo_model *m, int max_launches);
+int zo_profile_end(zo_model *m, double *ms, uint64_t *launches, double *work);
+
 int zo_free(zo_model *m);
 const char *zo_last_error(void);
 

@@ -21,6 +21,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 EXPORTS = (
     "zo_workspace_bytes", "zo_init_model", "zo_perturb", "zo_dual_forward", "zo_step", "zo_stream_block",
     "zo_stream_begin", "zo_stream_end", "zo_flush_pending", "zo_device_flags", "zo_free", "zo_last_error",
+    "zo_profile_begin", "zo_profile_end",
     "zo_kernel_z", "zo_kernel_normal_pairs", "zo_kernel_axpy_z", "zo_kernel_stage_pm", "zo_kernel_linear_pm",
     "zo_kernel_layernorm_pm", "zo_kernel_attention", "zo_kernel_lmhead_scratch_bytes", "zo_kernel_lmhead_ce",
 )
@@ -65,6 +66,8 @@ def lib():
         L.zo_flush_pending.argtypes = [vp]
         L.zo_device_flags.argtypes = [vp, ctypes.POINTER(u32)]
         L.zo_free.argtypes = [vp]
+        L.zo_profile_begin.argtypes = [vp, i32]
+        L.zo_profile_end.argtypes = [vp, vp, vp, vp]
         L.zo_kernel_z.argtypes = [vp, u64, u64, u32, u64, vp]
         L.zo_kernel_normal_pairs.argtypes = [vp, vp, u64, vp]
         L.zo_kernel_axpy_z.argtypes = [vp, vp, i32, u64, u64, u32, f32, vp, vp]
@@ -168,6 +171,21 @@ def zo_device_flags(model):
     v = ctypes.c_uint32()
     _check(lib().zo_device_flags(model, ctypes.byref(v)))
     return v.value
+
+
+ZO_K_NAMES = ("linear", "attention", "stage", "update", "norm", "ce", "other")
+
+
+def zo_profile_begin(model, max_launches):
+    _check(lib().zo_profile_begin(model, max_launches))
+
+
+def zo_profile_end(model):
+    """Returns {class name: (milliseconds, launches, algorithmic work)}."""
+    n = len(ZO_K_NAMES)
+    ms, cnt, work = (ctypes.c_double * n)(), (ctypes.c_uint64 * n)(), (ctypes.c_double * n)()
+    _check(lib().zo_profile_end(model, ctypes.addressof(ms), ctypes.addressof(cnt), ctypes.addressof(work)))
+    return {ZO_K_NAMES[i]: (ms[i], int(cnt[i]), work[i]) for i in range(n)}
 
 
 def zo_free(model):

@@ -44,6 +44,7 @@ extern "C" const char *zo_last_error(void) { return g_err; }
 namespace {
 
 constexpr int kPerBlock = 16;
+enum { K_LINEAR = ZO_K_LINEAR, K_ATTN = ZO_K_ATTENTION, K_STAGE = ZO_K_STAGE, K_UPDATE = ZO_K_UPDATE, K_NORM = ZO_K_NORM, K_CE = ZO_K_CE, K_OTHER = ZO_K_OTHER };
 enum { T_LN1G, T_LN1B, T_WQ, T_BQ, T_WK, T_BK, T_WV, T_BV, T_WO, T_BO, T_LN2G, T_LN2B, T_W1, T_B1, T_W2, T_B2 };
 enum SlotState { SLOT_EMPTY, SLOT_UPLOADED, SLOT_COMPUTED };
 
@@ -161,11 +162,40 @@ struct zo_model {
     uint64_t step_seed;
     float step_eps;
     int step_batch, step_seq;
+    // per-launch timing (zo_profile_begin / zo_profile_end)
+    bool prof_on;
+    int prof_n;
+    std::vector<hipEvent_t> prof_ev;      // 2 per record
+    std::vector<int> prof_cls;
+    std::vector<double> prof_work;
 };
 
 namespace {
 
 template <typename T> T *wsp_ptr(zo_model *m, size_t off) { return (T *)(m->ws + off); }
+
+// Brackets one kernel launch with events on the compute stream while profiling is on.
+struct ProfScope {
+    zo_model *m;
+    bool live;
+    ProfScope(zo_model *m_, int cls, double work) : m(m_), live(false)
+    {
+        if (!m->prof_on || 2 * (m->prof_n + 1) > (int)m->prof_ev.size()) return;
+        if (hipEventRecord(m->prof_ev[2 * m->prof_n], m->compute) != hipSuccess) return;
+        m->prof_cls[m->prof_n] = cls;
+        m->prof_work[m->prof_n] = work;
+        live = true;
+    }
+    ~ProfScope()
+    {
+        if (live && hipEventRecord(m->prof_ev[2 * m->prof_n + 1], m->compute) == hipSuccess) ++m->prof_n;
+    }
+};
+#define ZO_PROF(m, cls, work, expr)       \
+    do {                                  \
+        ProfScope scope__(m, cls, work);  \
+        ZO_HIP(expr);                     \
+    } while (0)
 
 size_t tensor_numel(const zo_config &c, const BlockLayout &L, int t)
 {
@@ -195,8 +225,10 @@ int axpy_range(zo_model *m, int first, int n, uint64_t seed, float scale, const 
     if (n <= 0) return ZO_OK;
     const uint64_t c0 = m->descs[first].first_chunk;
     const uint64_t c1 = first + n < m->n_tensors ? m->descs[first + n].first_chunk : m->total_chunks;
-    ZO_HIP(launch_axpy_multi(wsp_ptr<TensorDesc>(m, m->wsp.descs) + first, n, c0, c1 - c0, m->cfg.dtype, seed, scale, dev_scale,
-                             m->compute));
+    double bytes = 0;
+    for (int t = first; t < first + n; ++t) bytes += 2.0 * (double)m->descs[t].numel * elem_bytes(m->cfg.dtype);
+    ZO_PROF(m, K_UPDATE, bytes, launch_axpy_multi(wsp_ptr<TensorDesc>(m, m->wsp.descs) + first, n, c0, c1 - c0, m->cfg.dtype, seed, scale,
+                                                  dev_scale, m->compute));
     return ZO_OK;
 }
 
@@ -216,7 +248,8 @@ int stage_globals(zo_model *m, int seq, uint64_t seed, float eps)
     stage_batch_add(b, m->tptr[lnf], m->ws + m->wsp.lnf_pm[0], m->ws + m->wsp.lnf_pm[1], 1, c.d_model, lnf, false);
     stage_batch_add(b, m->tptr[lnf + 1], m->ws + m->wsp.lnf_pm[0] + c.d_model * e, m->ws + m->wsp.lnf_pm[1] + c.d_model * e, 1,
                     c.d_model, lnf + 1, false);
-    ZO_HIP(launch_stage(b, c.dtype, seed, eps, false, m->compute));
+    const double bytes = 3.0 * e * ((double)c.vocab * c.d_model + (double)seq * c.d_model + 2.0 * c.d_model);
+    ZO_PROF(m, K_STAGE, bytes, launch_stage(b, c.dtype, seed, eps, false, m->compute));
     return ZO_OK;
 }
 
@@ -242,7 +275,7 @@ int stage_block(zo_model *m, int layer, const char *slot_base, uint64_t seed, fl
     add(T_LN2G, L.st_ln2g, false); add(T_LN2B, L.st_ln2b, false);
     add(T_W1, L.st_w1, true); add(T_B1, L.st_b1, false);
     add(T_W2, L.st_w2, true); add(T_B2, L.st_b2, false);
-    ZO_HIP(launch_stage(b, c.dtype, seed, eps, single, m->compute));
+    ZO_PROF(m, K_STAGE, (single ? 2.0 : 3.0) * e * (double)L.total, launch_stage(b, c.dtype, seed, eps, single, m->compute));
     return ZO_OK;
 }
 
@@ -258,25 +291,28 @@ int block_forward(zo_model *m, int n_sign, int batch, int seq)
          *mid = m->ws + m->wsp.mid;
     hipStream_t s = m->compute;
     auto at = [&](const char *base, size_t off) { return (const void *)(base + off * e); };
-    ZO_HIP(launch_layernorm(resid, at(P, L.st_ln1g), at(M, L.st_ln1g), at(P, L.st_ln1b), at(M, L.st_ln1b), x, dt, n_sign, m_half, d,
-                            c.ln_eps, s));
-    ZO_HIP(launch_linear(x, at(P, L.st_wqkv), at(M, L.st_wqkv), at(P, L.st_bqkv), at(M, L.st_bqkv), qkv, dt, n_sign, m_half, 3 * d, d, 0,
-                         m->use_mfma, s));
-    ZO_HIP(launch_attention(qkv, att, dt, n_sign * batch, seq, c.n_heads, d / c.n_heads, m->use_mfma, s));
-    ZO_HIP(launch_linear(att, at(P, L.st_wo), at(M, L.st_wo), at(P, L.st_bo), at(M, L.st_bo), resid, dt, n_sign, m_half, d, d, 2,
-                         m->use_mfma, s));
-    ZO_HIP(launch_layernorm(resid, at(P, L.st_ln2g), at(M, L.st_ln2g), at(P, L.st_ln2b), at(M, L.st_ln2b), x, dt, n_sign, m_half, d,
-                            c.ln_eps, s));
-    ZO_HIP(launch_linear(x, at(P, L.st_w1), at(M, L.st_w1), at(P, L.st_b1), at(M, L.st_b1), mid, dt, n_sign, m_half, f, d, 1,
-                         m->use_mfma, s));
-    ZO_HIP(launch_linear(mid, at(P, L.st_w2), at(M, L.st_w2), at(P, L.st_b2), at(M, L.st_b2), resid, dt, n_sign, m_half, d, f, 2,
-                         m->use_mfma, s));
+    const double rows = (double)n_sign * m_half;
+    const double ln_bytes = rows * d * (resid_bytes(dt) + act_bytes(dt));
+    const double attn_flops = 2.0 * (double)n_sign * batch * c.n_heads * ((double)seq * (seq + 1)) * (d / c.n_heads);
+    ZO_PROF(m, K_NORM, ln_bytes, launch_layernorm(resid, at(P, L.st_ln1g), at(M, L.st_ln1g), at(P, L.st_ln1b), at(M, L.st_ln1b), x, dt,
+                                                  n_sign, m_half, d, c.ln_eps, s));
+    ZO_PROF(m, K_LINEAR, 2.0 * rows * 3 * d * d, launch_linear(x, at(P, L.st_wqkv), at(M, L.st_wqkv), at(P, L.st_bqkv), at(M, L.st_bqkv),
+                                                               qkv, dt, n_sign, m_half, 3 * d, d, 0, m->use_mfma, s));
+    ZO_PROF(m, K_ATTN, attn_flops, launch_attention(qkv, att, dt, n_sign * batch, seq, c.n_heads, d / c.n_heads, m->use_mfma, s));
+    ZO_PROF(m, K_LINEAR, 2.0 * rows * d * d, launch_linear(att, at(P, L.st_wo), at(M, L.st_wo), at(P, L.st_bo), at(M, L.st_bo), resid, dt,
+                                                           n_sign, m_half, d, d, 2, m->use_mfma, s));
+    ZO_PROF(m, K_NORM, ln_bytes, launch_layernorm(resid, at(P, L.st_ln2g), at(M, L.st_ln2g), at(P, L.st_ln2b), at(M, L.st_ln2b), x, dt,
+                                                  n_sign, m_half, d, c.ln_eps, s));
+    ZO_PROF(m, K_LINEAR, 2.0 * rows * d * f, launch_linear(x, at(P, L.st_w1), at(M, L.st_w1), at(P, L.st_b1), at(M, L.st_b1), mid, dt,
+                                                           n_sign, m_half, f, d, 1, m->use_mfma, s));
+    ZO_PROF(m, K_LINEAR, 2.0 * rows * d * f, launch_linear(mid, at(P, L.st_w2), at(M, L.st_w2), at(P, L.st_b2), at(M, L.st_b2), resid, dt,
+                                                           n_sign, m_half, d, f, 2, m->use_mfma, s));
     return ZO_OK;
 }
 
 // LM head (tied) + cross entropy over row chunks.  x: final-LayerNormed activations [n_sign*m_half, d].
-int lmhead_ce(hipStream_t s, const void *x, const void *e_p, const void *e_m, const int32_t *target, double *row_loss, void *logits,
-              int logits_rows, int dtype, int n_sign, int m_half, int d, int vocab, bool use_mfma)
+int lmhead_ce(zo_model *prof, hipStream_t s, const void *x, const void *e_p, const void *e_m, const int32_t *target, double *row_loss,
+              void *logits, int logits_rows, int dtype, int n_sign, int m_half, int d, int vocab, bool use_mfma)
 {
     const size_t ab = act_bytes(dtype);
     for (int sign = 0; sign < n_sign; ++sign) {
@@ -285,8 +321,13 @@ int lmhead_ce(hipStream_t s, const void *x, const void *e_p, const void *e_m, co
             const int nr = m_half - r0 < logits_rows ? m_half - r0 : logits_rows;
             const size_t row = (size_t)sign * m_half + r0;
             const char *xa = (const char *)x + row * d * ab;
-            ZO_HIP(launch_linear(xa, wt, wt, nullptr, nullptr, logits, dtype, 1, nr, vocab, d, 3, use_mfma, s));
-            ZO_HIP(launch_ce_rows(logits, target + row, row_loss + row, dtype, nr, vocab, s));
+            if (prof) {
+                ZO_PROF(prof, K_LINEAR, 2.0 * nr * (double)vocab * d, launch_linear(xa, wt, wt, nullptr, nullptr, logits, dtype, 1, nr, vocab, d, 3, use_mfma, s));
+                ZO_PROF(prof, K_CE, (double)nr * vocab * acc_bytes(dtype), launch_ce_rows(logits, target + row, row_loss + row, dtype, nr, vocab, s));
+            } else {
+                ZO_HIP(launch_linear(xa, wt, wt, nullptr, nullptr, logits, dtype, 1, nr, vocab, d, 3, use_mfma, s));
+                ZO_HIP(launch_ce_rows(logits, target + row, row_loss + row, dtype, nr, vocab, s));
+            }
         }
     }
     return ZO_OK;
@@ -301,19 +342,21 @@ int head_and_loss(zo_model *m, int n_sign, int batch, int seq, const void *e_p, 
     void *resid = m->ws + m->wsp.resid, *x = m->ws + m->wsp.xbuf;
     int32_t *target = wsp_ptr<int32_t>(m, m->wsp.target);
     double *row_loss = wsp_ptr<double>(m, m->wsp.row_loss);
-    ZO_HIP(launch_layernorm(resid, lnf_p, lnf_m, (const char *)lnf_p + d * e, (const char *)lnf_m + d * e, x, c.dtype, n_sign, m_half, d,
-                            c.ln_eps, m->compute));
-    ZO_TRY(lmhead_ce(m->compute, x, e_p, e_m, target, row_loss, m->ws + m->wsp.logits, m->wsp.logits_rows, c.dtype, n_sign, m_half, d,
+    ZO_PROF(m, K_NORM, (double)n_sign * m_half * d * (resid_bytes(c.dtype) + act_bytes(c.dtype)),
+            launch_layernorm(resid, lnf_p, lnf_m, (const char *)lnf_p + d * e, (const char *)lnf_m + d * e, x, c.dtype, n_sign, m_half, d,
+                             c.ln_eps, m->compute));
+    ZO_TRY(lmhead_ce(m, m->compute, x, e_p, e_m, target, row_loss, m->ws + m->wsp.logits, m->wsp.logits_rows, c.dtype, n_sign, m_half, d,
                      c.vocab, m->use_mfma));
-    ZO_HIP(launch_loss_reduce(row_loss, n_sign, m_half, batch * (seq - 1), loss_out, m->compute));
+    ZO_PROF(m, K_OTHER, 8.0 * n_sign * m_half, launch_loss_reduce(row_loss, n_sign, m_half, batch * (seq - 1), loss_out, m->compute));
     return ZO_OK;
 }
 
 int embed(zo_model *m, const int32_t *tokens, int n_sign, int batch, int seq, const void *e_p, const void *e_m, const void *pos_p,
           const void *pos_m)
 {
-    ZO_HIP(launch_embed(tokens, e_p, e_m, pos_p, pos_m, m->ws + m->wsp.resid, wsp_ptr<int32_t>(m, m->wsp.target), m->flags,
-                        m->cfg.dtype, n_sign, batch, seq, m->cfg.d_model, m->cfg.vocab, m->compute));
+    ZO_PROF(m, K_OTHER, (double)n_sign * batch * seq * m->cfg.d_model * (2.0 * elem_bytes(m->cfg.dtype) + resid_bytes(m->cfg.dtype)),
+            launch_embed(tokens, e_p, e_m, pos_p, pos_m, m->ws + m->wsp.resid, wsp_ptr<int32_t>(m, m->wsp.target), m->flags, m->cfg.dtype,
+                         n_sign, batch, seq, m->cfg.d_model, m->cfg.vocab, m->compute));
     return ZO_OK;
 }
 
@@ -510,7 +553,7 @@ extern "C" int zo_init_model(const zo_config *cfg, void *const *tensor_ptrs, int
     hipError_t err = hipMemcpy(m->ws + wsp.descs, m->descs.data(), sizeof(TensorDesc) * n_tensors, hipMemcpyHostToDevice);
     if (err == hipSuccess) err = hipMemset(sc, 0, 256);
     if (err != hipSuccess) { delete m; return fail(ZO_EHIP, "initialising the workspace failed: %s", hipGetErrorString(err)); }
-    m->pending = false; m->step_open = false; m->next_block = 0;
+    m->pending = false; m->step_open = false; m->next_block = 0; m->prof_on = false; m->prof_n = 0;
     for (int s = 0; s < 2; ++s) {
         m->slot_block[s] = -1; m->slot_state[s] = SLOT_EMPTY; m->slot_dirty[s] = false;
         m->ev_uploaded[s] = m->ev_staged[s] = m->ev_written[s] = nullptr;
@@ -543,6 +586,7 @@ extern "C" int zo_free(zo_model *m)
         if (m->ev_written[s]) (void)hipEventDestroy(m->ev_written[s]);
     }
     if (m->own_download) (void)hipStreamDestroy(m->download);
+    for (hipEvent_t ev : m->prof_ev) (void)hipEventDestroy(ev);
     delete m;
     return ZO_OK;
 }
@@ -671,6 +715,38 @@ extern "C" int zo_device_flags(zo_model *m, uint32_t *host_flags)
     return ZO_OK;
 }
 
+extern "C" int zo_profile_begin(zo_model *m, int max_launches)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    if (max_launches < 1 || max_launches > (1 << 20)) return fail(ZO_EINVAL, "max_launches %d out of range", max_launches);
+    while ((int)m->prof_ev.size() < 2 * max_launches) {
+        hipEvent_t ev;
+        ZO_HIP(hipEventCreate(&ev));
+        m->prof_ev.push_back(ev);
+    }
+    m->prof_cls.assign(max_launches, 0);
+    m->prof_work.assign(max_launches, 0.0);
+    m->prof_n = 0;
+    m->prof_on = true;
+    return ZO_OK;
+}
+
+extern "C" int zo_profile_end(zo_model *m, double *ms, uint64_t *launches, double *work)
+{
+    if (!m || !ms || !launches || !work) return fail(ZO_EINVAL, "NULL argument");
+    if (!m->prof_on) return fail(ZO_ESTATE, "profiling was not started");
+    m->prof_on = false;
+    ZO_HIP(hipStreamSynchronize(m->compute));
+    for (int c = 0; c < ZO_K_CLASSES; ++c) { ms[c] = 0.0; launches[c] = 0; work[c] = 0.0; }
+    for (int i = 0; i < m->prof_n; ++i) {
+        float t = 0.0f;
+        ZO_HIP(hipEventElapsedTime(&t, m->prof_ev[2 * i], m->prof_ev[2 * i + 1]));
+        const int c = m->prof_cls[i];
+        ms[c] += t; launches[c] += 1; work[c] += m->prof_work[i];
+    }
+    return ZO_OK;
+}
+
 // ------------------------------------------------------------------ kernel-level entry points
 static int check_dtype(int dtype) { return dtype >= 0 && dtype <= 2 ? ZO_OK : fail(ZO_EINVAL, "dtype %d unknown", dtype); }
 
@@ -762,5 +838,5 @@ extern "C" int zo_kernel_lmhead_ce(const void *x, const void *e_plus, const void
     if (!x || !e_plus || !e_minus || !target || !row_loss || !scratch) return fail(ZO_EINVAL, "NULL argument");
     if (m_half < 1 || d < 1 || vocab < 2) return fail(ZO_EINVAL, "bad shape");
     if (dtype != ZO_FP32 && (d % 8 || vocab % 8)) return fail(ZO_EINVAL, "d and vocab must be multiples of 8 for 2-byte types");
-    return lmhead_ce((hipStream_t)stream, x, e_plus, e_minus, target, row_loss, scratch, lmhead_rows(m_half), dtype, 2, m_half, d, vocab, true);
+    return lmhead_ce(nullptr, (hipStream_t)stream, x, e_plus, e_minus, target, row_loss, scratch, lmhead_rows(m_half), dtype, 2, m_half, d, vocab, true);
 }
