@@ -11,9 +11,15 @@
 // activation tile the B operand, so a lane's 16 accumulators are 4 runs of 4 consecutive n of
 // one output row, which makes the epilogue 8/16-byte stores.
 //
-// Tiling: 128 (rows) x 128 (n) x 64 (k) per workgroup of 4 waves (2 x 2, 64 x 64 each, i.e.
-// 2 x 2 MFMA tiles of 32 x 32), LDS double-buffered, 16-byte chunks XOR-swizzled by row so
-// that the 32 rows a fragment load touches spread over all banks.
+// Two tilings:
+//  * 256 x 256 x 32, 4 waves of 128 x 128 (4 x 4 MFMA tiles, 256 accumulator registers), one
+//    workgroup per CU.  Operand tiles go from global memory straight into LDS
+//    (global_load_lds_dwordx4, no register staging) through a 4-stage ring of 32 KiB stages, so
+//    three k-slabs are in flight while one is multiplied; 16-byte chunks are XOR-swizzled on the
+//    global side so that fragment reads spread over the banks.  Workgroups are renumbered so that
+//    each XCD (its own L2) owns a contiguous band of 8 tile-rows and walks it column by column.
+//  * 128 x 128 x 64, 4 waves of 64 x 64, register-staged double buffer: for shapes with too few
+//    256-tiles to fill 256 CUs and for ragged small cases.
 #include "zo_kernels.h"
 #include "zo_types.hip.h"
 
@@ -34,6 +40,38 @@ template <int DT> __device__ __forceinline__ f32x16 mfma32(const uint4 &a, const
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     else
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+
+// One lane's run of 4 consecutive n of one output row.
+template <int DT, int EPI>
+__device__ __forceinline__ void epilogue_store(float (&v)[4], const uint16_t *__restrict__ bias, void *__restrict__ y, size_t row,
+                                               int n, int nc)
+{
+    if constexpr (EPI != 3) {
+        const uint2 braw = *(const uint2 *)(bias + nc);
+        const uint16_t bb[4] = {(uint16_t)(braw.x & 0xffff), (uint16_t)(braw.x >> 16), (uint16_t)(braw.y & 0xffff),
+                                (uint16_t)(braw.y >> 16)};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] += Prec<DT>::w2f(bb[e]);
+    }
+    if constexpr (EPI == 0 || EPI == 1) {
+        if constexpr (EPI == 1) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+        }
+        uint2 o;
+        o.x = (uint32_t)Prec<DT>::acc2a(v[0]) | ((uint32_t)Prec<DT>::acc2a(v[1]) << 16);
+        o.y = (uint32_t)Prec<DT>::acc2a(v[2]) | ((uint32_t)Prec<DT>::acc2a(v[3]) << 16);
+        *(uint2 *)((uint16_t *)y + row * n + nc) = o;
+    } else if constexpr (EPI == 2) {
+        float4 *p = (float4 *)((float *)y + row * n + nc);
+        float4 h = *p;
+        h.x += v[0]; h.y += v[1]; h.z += v[2]; h.w += v[3];
+        *p = h;
+    } else {
+        *(float4 *)((float *)y + row * n + nc) = float4{v[0], v[1], v[2], v[3]};
+    }
 }
 
 // LDS tile: [rows][8 chunks] of uint4, chunk c of row r stored at c ^ (r & 7).
@@ -129,34 +167,136 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__rest
                 float v[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = acc[tn][tm][4 * g + e];
-                if constexpr (EPI != 3) {
-                    const uint2 braw = *(const uint2 *)(bias + nc);
-                    const uint16_t bb[4] = {(uint16_t)(braw.x & 0xffff), (uint16_t)(braw.x >> 16),
-                                            (uint16_t)(braw.y & 0xffff), (uint16_t)(braw.y >> 16)};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] += Prec<DT>::w2f(bb[e]);
-                }
-                if constexpr (EPI == 0 || EPI == 1) {
-                    if constexpr (EPI == 1) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
-                    }
-                    uint2 o;
-                    o.x = (uint32_t)Prec<DT>::acc2a(v[0]) | ((uint32_t)Prec<DT>::acc2a(v[1]) << 16);
-                    o.y = (uint32_t)Prec<DT>::acc2a(v[2]) | ((uint32_t)Prec<DT>::acc2a(v[3]) << 16);
-                    *(uint2 *)((uint16_t *)y + row * n + nc) = o;
-                } else if constexpr (EPI == 2) {
-                    float4 *p = (float4 *)((float *)y + row * n + nc);
-                    float4 h = *p;
-                    h.x += v[0]; h.y += v[1]; h.z += v[2]; h.w += v[3];
-                    *p = h;
-                } else {
-                    *(float4 *)((float *)y + row * n + nc) = float4{v[0], v[1], v[2], v[3]};
-                }
+                epilogue_store<DT, EPI>(v, bias, y, row, n, nc);
             }
         }
     }
 }
+
+
+// ------------------------------------------------------------------ 256 x 256 x 32 tiling
+namespace big {
+
+constexpr int BM = 256, BN = 256, BK = 32, ST = 4;
+constexpr int kTileU4 = BM * (BK / 8);          // uint4 per operand tile (1024)
+constexpr int kStageU4 = 2 * kTileU4;           // x tile then w tile
+constexpr int kLdsBytes = ST * kStageU4 * 16;   // 128 KiB
+constexpr int kGroupM = 8;                      // tile-rows per band
+
+// 16 bytes per lane from global memory straight into LDS: lane L lands at lds_off + 16 L.
+// Issued from asm so that the waits are ours: the compiler would otherwise drain every
+// outstanding load before the next LDS read, which defeats the multi-stage ring.
+__device__ __forceinline__ void gload_lds16(const void *gptr, uint32_t lds_off)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory");
+}
+
+template <int DT, int EPI>
+__global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ wt_p,
+                                                             const uint16_t *__restrict__ wt_m, const uint16_t *__restrict__ b_p,
+                                                             const uint16_t *__restrict__ b_m, void *__restrict__ y, int m_half,
+                                                             int n, int k, int n_sign, int tiles_m, int tiles_n, int total)
+{
+    extern __shared__ __attribute__((aligned(16))) uint4 smem[];
+    // XCD-aware renumbering: hardware deals consecutive workgroup ids round-robin to the 8 XCDs.
+    const int per_xcd = (total + 7) / 8;
+    const int lin = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
+    if (lin >= total) return;
+    const int rows_total = n_sign * tiles_m;            // tile-rows over both signs
+    const int band = lin / (kGroupM * tiles_n), rem = lin % (kGroupM * tiles_n);
+    const int band_rows = rows_total - band * kGroupM < kGroupM ? rows_total - band * kGroupM : kGroupM;
+    const int trow = band * kGroupM + rem % band_rows, tcol = rem / band_rows;
+    const int sign = trow / tiles_m, tm_idx = trow % tiles_m;
+
+    const uint16_t *xa = x + (size_t)sign * m_half * k;
+    const uint16_t *wt = sign ? wt_m : wt_p;
+    const uint16_t *bias = sign ? b_m : b_p;
+    const int m0 = tm_idx * BM, n0 = tcol * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // load assignment: wave w, instruction i covers tile rows (4 w + i) * 16 .. + 15; lane -> (row, slot)
+    const uint16_t *xg[4], *wg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = (wave * 4 + i) * 16 + (lane >> 2), slot = lane & 3;
+        const int chunk = slot ^ ((row >> 1) & 3);
+        int xr = m0 + row; xr = xr < m_half ? xr : m_half - 1;       // clamp: masked at the store
+        int wr = n0 + row; wr = wr < n ? wr : n - 1;
+        xg[i] = xa + (size_t)xr * k + chunk * 8;
+        wg[i] = wt + (size_t)wr * k + chunk * 8;
+    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
+    const int nk = k / BK;
+    auto issue = [&](int t) {
+        const int k0 = (t < nk ? t : nk - 1) * BK;                   // past the end: reload the last slab (never read)
+        const uint32_t st = lds_base + (uint32_t)(t % ST) * (kStageU4 * 16) + (uint32_t)wave * 4096u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            gload_lds16(xg[i] + k0, st + i * 1024u);
+            gload_lds16(wg[i] + k0, st + kTileU4 * 16 + i * 1024u);
+        }
+    };
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+
+    issue(0);
+    issue(1);
+    issue(2);
+    const int fr = lane & 31, fh = lane >> 5, sw = (fr >> 1) & 3;
+    const int xrow = (wm * 128 + fr) * 4, wrow = (wn * 128 + fr) * 4;     // uint4 index of the lane's first rows
+    for (int kt = 0; kt < nk; ++kt) {
+        // slabs kt+1 and kt+2 (8 loads each) may stay in flight; slab kt must have landed, for every wave
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        issue(kt + 3);                                               // overwrites the stage read in iteration kt-1
+        const uint4 *xs = smem + (kt % ST) * kStageU4;
+        const uint4 *ws = xs + kTileU4;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int slot = (2 * ks + fh) ^ sw;
+            uint4 wf[4], xf[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                wf[t] = ws[wrow + t * 128 + slot];
+                xf[t] = xs[xrow + t * 128 + slot];
+            }
+#pragma unroll
+            for (int tn = 0; tn < 4; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < 4; ++tm) acc[tn][tm] = mfma32<DT>(wf[tn], xf[tm], acc[tn][tm]);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // drain the tail loads before LDS is released
+
+#pragma unroll
+    for (int tm = 0; tm < 4; ++tm) {
+        const int mr = m0 + wm * 128 + tm * 32 + fr;
+        if (mr >= m_half) continue;
+        const size_t row = (size_t)sign * m_half + mr;
+#pragma unroll
+        for (int tn = 0; tn < 4; ++tn) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int nc = n0 + wn * 128 + tn * 32 + 8 * g + 4 * fh;
+                if (nc >= n) continue;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[tn][tm][4 * g + e];
+                epilogue_store<DT, EPI>(v, bias, y, row, n, nc);
+            }
+        }
+    }
+}
+
+}  // namespace big
 
 template <int DT>
 void launch_t(const void *x, const void *wt_p, const void *wt_m, const void *b_p, const void *b_m, void *y, int n_sign,
@@ -175,6 +315,44 @@ void launch_t(const void *x, const void *wt_p, const void *wt_m, const void *b_p
 #undef ZO_L
 }
 
+template <int DT>
+hipError_t launch_big_t(const void *x, const void *wt_p, const void *wt_m, const void *b_p, const void *b_m, void *y, int n_sign,
+                        int m_half, int n, int k, int epi, hipStream_t s)
+{
+    const int tiles_m = (m_half + big::BM - 1) / big::BM, tiles_n = (n + big::BN - 1) / big::BN;
+    const int total = n_sign * tiles_m * tiles_n;
+    const dim3 grid((total + 7) / 8 * 8), block(256);
+#define ZO_B(E)                                                                                                                  \
+    {                                                                                                                            \
+        auto kern = big::linear_mfma256_kernel<DT, E>;                                                                           \
+        static bool attr_set = false;                                                                                            \
+        if (!attr_set) {                                                                                                         \
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, big::kLdsBytes);  \
+            if (e != hipSuccess) return e;                                                                                       \
+            attr_set = true;                                                                                                     \
+        }                                                                                                                        \
+        kern<<<grid, block, big::kLdsBytes, s>>>((const uint16_t *)x, (const uint16_t *)wt_p, (const uint16_t *)wt_m,            \
+                                                 (const uint16_t *)b_p, (const uint16_t *)b_m, y, m_half, n, k, n_sign, tiles_m,  \
+                                                 tiles_n, total);                                                                         \
+    }
+    switch (epi) {
+    case 0: ZO_B(0) break;
+    case 1: ZO_B(1) break;
+    case 2: ZO_B(2) break;
+    default: ZO_B(3) break;
+    }
+#undef ZO_B
+    return hipGetLastError();
+}
+
+// The big tiling pays once there are enough 256-tiles to keep 256 CUs busy.
+bool use_big(int n_sign, int m_half, int n, int k)
+{
+    if (k % big::BK) return false;
+    const long tiles = (long)n_sign * ((m_half + big::BM - 1) / big::BM) * ((n + big::BN - 1) / big::BN);
+    return tiles >= 384;
+}
+
 }  // namespace
 
 bool mfma_linear_supported(int m_half, int n, int k) { return m_half >= 1 && n >= 8 && n % 8 == 0 && k >= BK && k % BK == 0; }
@@ -183,6 +361,10 @@ hipError_t launch_linear_mfma(const void *x, const void *wt_p, const void *wt_m,
                               int dtype, int n_sign, int m_half, int n, int k, int epilogue, hipStream_t s)
 {
     if (!mfma_linear_supported(m_half, n, k) || (dtype != kBF16 && dtype != kFP16)) return hipErrorInvalidValue;
+    if (use_big(n_sign, m_half, n, k)) {
+        return dtype == kBF16 ? launch_big_t<kBF16>(x, wt_p, wt_m, b_p, b_m, y, n_sign, m_half, n, k, epilogue, s)
+                              : launch_big_t<kFP16>(x, wt_p, wt_m, b_p, b_m, y, n_sign, m_half, n, k, epilogue, s);
+    }
     if (dtype == kBF16) launch_t<kBF16>(x, wt_p, wt_m, b_p, b_m, y, n_sign, m_half, n, k, epilogue, s);
     else launch_t<kFP16>(x, wt_p, wt_m, b_p, b_m, y, n_sign, m_half, n, k, epilogue, s);
     return hipGetLastError();
