@@ -28,6 +28,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="opt-13b", help="tiny | opt-125m | opt-1.3b | opt-13b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run one 1 GiB device-to-device copy, a kernel of known HBM traffic that calibrates "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters in the same run")
     return ap.parse_args()
 
 
@@ -157,6 +160,13 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = zo_amd.zo_profile_end(h)
+    if args.traffic_probe:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        a.copy_(b)
+        torch.cuda.synchronize()
+        del a, b
     lp, lm, g = zo_amd.zo_step(h, tokens, c["batch"], c["seq"], 10**6, c["eps"], c["lr"])
     flags = zo_amd.zo_device_flags(h)
     zo_amd.zo_free(h)

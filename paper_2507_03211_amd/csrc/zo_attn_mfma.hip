@@ -42,10 +42,11 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
                                                         int n_heads)
 {
     constexpr int CH = DH / 8;            // 16-byte chunks per K row
-    constexpr int VLD = BKV + 8;          // padded V^T row (elements)
-    __shared__ uint4 ks[BKV * CH];        // K tile, chunk c of key r at c ^ (r & 7)
+    constexpr int VLD = BKV + 4;          // padded V^T row: 34 banks, so 32 lanes reading 8 bytes each spread over all 64
+    __shared__ uint4 ks[BKV * CH];        // K tile, chunk c of key r at c ^ kswz(r): 16 rows -> 16 distinct bank groups
     __shared__ __attribute__((aligned(16))) uint16_t vt[DH * VLD];   // V^T tile: [channel][key]
 
+    auto kswz = [](int r) { return DH == 128 ? (r & 15) : ((r >> 1) & 7); };
     const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;             // long rows first
     const int head = blockIdx.y, sq = blockIdx.z;
     const int d = n_heads * DH, ld = 3 * d;
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int c = lch + 4 * i;
-            ks[lkey * CH + (c ^ (lkey & 7))] = kreg[i];
+            ks[lkey * CH + (c ^ kswz(lkey))] = kreg[i];
             const uint32_t w[4] = {vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
 #pragma unroll
             for (int s = 0; s < DH / 16; ++s) {
                 const int r = kt * 32 + fr;
-                const uint4 kf = ks[r * CH + ((2 * s + fh) ^ (r & 7))];
+                const uint4 kf = ks[r * CH + ((2 * s + fh) ^ kswz(r))];
                 sacc[kt] = mfma32<DT>(kf, qf[s], sacc[kt]);
             }
         }

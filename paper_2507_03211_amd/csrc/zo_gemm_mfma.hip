@@ -12,11 +12,11 @@
 // one output row, which makes the epilogue 8/16-byte stores.
 //
 // Two tilings:
-//  * 256 x 256 x 32, 4 waves of 128 x 128 (4 x 4 MFMA tiles, 256 accumulator registers), one
+//  * 256 x 256 x 64, 4 waves of 128 x 128 (4 x 4 MFMA tiles, 256 accumulator registers), one
 //    workgroup per CU.  Operand tiles go from global memory straight into LDS
-//    (global_load_lds_dwordx4, no register staging) through a 4-stage ring of 32 KiB stages, so
-//    three k-slabs are in flight while one is multiplied; 16-byte chunks are XOR-swizzled on the
-//    global side so that fragment reads spread over the banks.  Workgroups are renumbered so that
+//    (global_load_lds_dwordx4, no register staging), whole 128-byte lines per tile row, into two
+//    64 KiB stages: one slab is in flight while one is multiplied.  16-byte chunks are XOR-swizzled
+//    on the global side so that fragment reads are free of bank conflicts.  Workgroups are renumbered so that
 //    each XCD (its own L2) owns a contiguous band of 8 tile-rows and walks it column by column.
 //  * 128 x 128 x 64, 4 waves of 64 x 64, register-staged double buffer: for shapes with too few
 //    256-tiles to fill 256 CUs and for ragged small cases.
@@ -74,8 +74,10 @@ __device__ __forceinline__ void epilogue_store(float (&v)[4], const uint16_t *__
     }
 }
 
-// LDS tile: [rows][8 chunks] of uint4, chunk c of row r stored at c ^ (r & 7).
-__device__ __forceinline__ int lds_slot(int r, int c) { return r * kChunksPerRow + (c ^ (r & 7)); }
+// LDS tile: [rows][8 chunks] of uint4, chunk c of row r stored at c ^ ((r >> 1) & 7): the LDS has 64
+// four-byte banks, so 16 lanes (16 consecutive rows, one logical chunk) must land on 16 distinct 16-byte
+// positions of a 256-byte window, i.e. on distinct (row parity, slot) pairs.
+__device__ __forceinline__ int lds_slot(int r, int c) { return r * kChunksPerRow + (c ^ ((r >> 1) & 7)); }
 
 template <int DT, int EPI>
 __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ wt_p,
@@ -177,15 +179,15 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__rest
 // ------------------------------------------------------------------ 256 x 256 x 32 tiling
 namespace big {
 
-constexpr int BM = 256, BN = 256, BK = 32, ST = 4;
-constexpr int kTileU4 = BM * (BK / 8);          // uint4 per operand tile (1024)
+constexpr int BM = 256, BN = 256, BK = 64, ST = 2;
+constexpr int kTileU4 = BM * (BK / 8);          // uint4 per operand tile (2048)
 constexpr int kStageU4 = 2 * kTileU4;           // x tile then w tile
 constexpr int kLdsBytes = ST * kStageU4 * 16;   // 128 KiB
 constexpr int kGroupM = 8;                      // tile-rows per band
 
 // 16 bytes per lane from global memory straight into LDS: lane L lands at lds_off + 16 L.
 // Issued from asm so that the waits are ours: the compiler would otherwise drain every
-// outstanding load before the next LDS read, which defeats the multi-stage ring.
+// outstanding load before the next LDS read, which defeats the overlap.
 __device__ __forceinline__ void gload_lds16(const void *gptr, uint32_t lds_off)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory");
@@ -216,12 +218,16 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
 
-    // load assignment: wave w, instruction i covers tile rows (4 w + i) * 16 .. + 15; lane -> (row, slot)
-    const uint16_t *xg[4], *wg[4];
+    // Load assignment: one wave instruction moves 8 tile rows x 128 bytes (whole cache lines); wave w,
+    // instruction i covers rows (8 w + i) * 8 .. + 7; lane -> (row, 16-byte slot).  The slot holds logical
+    // chunk slot ^ (row / 2 mod 8): 16 consecutive rows of one logical chunk then sit on 16 distinct
+    // 16-byte positions of the 64-bank (256-byte wide) LDS, so fragment reads are conflict-free.
+    const int lrow = lane >> 3, lslot = lane & 7;
+    const uint16_t *xg[8], *wg[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = (wave * 4 + i) * 16 + (lane >> 2), slot = lane & 3;
-        const int chunk = slot ^ ((row >> 1) & 3);
+    for (int i = 0; i < 8; ++i) {
+        const int row = (wave * 8 + i) * 8 + lrow;
+        const int chunk = lslot ^ ((row >> 1) & 7);
         int xr = m0 + row; xr = xr < m_half ? xr : m_half - 1;       // clamp: masked at the store
         int wr = n0 + row; wr = wr < n ? wr : n - 1;
         xg[i] = xa + (size_t)xr * k + chunk * 8;
@@ -230,10 +236,10 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
     const int nk = k / BK;
     auto issue = [&](int t) {
-        const int k0 = (t < nk ? t : nk - 1) * BK;                   // past the end: reload the last slab (never read)
-        const uint32_t st = lds_base + (uint32_t)(t % ST) * (kStageU4 * 16) + (uint32_t)wave * 4096u;
+        const int k0 = (t < nk ? t : nk - 1) * BK;                   // past the end: reload the last slab (never multiplied)
+        const uint32_t st = lds_base + (uint32_t)(t % ST) * (kStageU4 * 16) + (uint32_t)wave * 8192u;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 8; ++i) {
             gload_lds16(xg[i] + k0, st + i * 1024u);
             gload_lds16(wg[i] + k0, st + kTileU4 * 16 + i * 1024u);
         }
@@ -247,31 +253,69 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
+    const int fr = lane & 31, fh = lane >> 5, sw = (fr >> 1) & 7;
+    const int xrow = (wm * 128 + fr) * 8, wrow = (wn * 128 + fr) * 8;     // uint4 index of the lane's first rows
+    uint4 wfa[4], xfa[4], wfb[4], xfb[4];                                 // two fragment sets: one multiplies while one loads
+    auto load_frags = [&](int slab, int ks, uint4 (&wf)[4], uint4 (&xf)[4]) {
+        const uint4 *xs = smem + (slab % ST) * kStageU4;
+        const uint4 *ws = xs + kTileU4;
+        const int slot = (2 * ks + fh) ^ sw;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            wf[t] = ws[wrow + t * 256 + slot];
+            xf[t] = xs[xrow + t * 256 + slot];
+        }
+    };
+    auto mma16 = [&](const uint4 (&wf)[4], const uint4 (&xf)[4]) {
+#pragma unroll
+        for (int tn = 0; tn < 4; ++tn)
+#pragma unroll
+            for (int tm = 0; tm < 4; ++tm) acc[tn][tm] = mfma32<DT>(wf[tn], xf[tm], acc[tn][tm]);
+    };
+
+    // Software pipeline over two 64 KiB stages.  The barrier sits before the last quarter of a slab's
+    // multiplies, once this wave's last LDS reads of slab kt are in registers: the stage is refilled with
+    // slab kt+2 at once, which then has the rest of this slab and three quarters of the next to land.
+    // sched_barrier(0) pins the order (the compiler would sink each LDS read down to its first use).
     issue(0);
     issue(1);
-    issue(2);
-    const int fr = lane & 31, fh = lane >> 5, sw = (fr >> 1) & 3;
-    const int xrow = (wm * 128 + fr) * 4, wrow = (wn * 128 + fr) * 4;     // uint4 index of the lane's first rows
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    load_frags(0, 0, wfa, xfa);
     for (int kt = 0; kt < nk; ++kt) {
-        // slabs kt+1 and kt+2 (8 loads each) may stay in flight; slab kt must have landed, for every wave
-        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        load_frags(kt, 1, wfb, xfb);
+        __builtin_amdgcn_sched_barrier(0);
+        mma16(wfa, xfa);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(kt, 2, wfa, xfa);
+        __builtin_amdgcn_sched_barrier(0);
+        mma16(wfb, xfb);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(kt, 3, wfb, xfb);
+        __builtin_amdgcn_sched_barrier(0);
+        mma16(wfa, xfa);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");    // slab kt+1 landed; slab kt fully in registers
         __builtin_amdgcn_s_barrier();
-        issue(kt + 3);                                               // overwrites the stage read in iteration kt-1
-        const uint4 *xs = smem + (kt % ST) * kStageU4;
-        const uint4 *ws = xs + kTileU4;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const int slot = (2 * ks + fh) ^ sw;
-            uint4 wf[4], xf[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                wf[t] = ws[wrow + t * 128 + slot];
-                xf[t] = xs[xrow + t * 128 + slot];
-            }
+        load_frags(kt + 1, 0, wfa, xfa);                                // past the end: a reloaded slab, never multiplied
+        __builtin_amdgcn_sched_barrier(0);
+        // refill the stage of slab kt, one load between two multiplies: a burst of 16 would hold the wave at
+        // the texture-address queue while the matrix pipe runs dry
+        {
+            const int t = kt + 2;
+            const int k0 = (t < nk ? t : nk - 1) * BK;
+            const uint32_t st = lds_base + (uint32_t)(t % ST) * (kStageU4 * 16) + (uint32_t)wave * 8192u;
 #pragma unroll
             for (int tn = 0; tn < 4; ++tn)
 #pragma unroll
-                for (int tm = 0; tm < 4; ++tm) acc[tn][tm] = mfma32<DT>(wf[tn], xf[tm], acc[tn][tm]);
+                for (int tm = 0; tm < 4; ++tm) {
+                    const int i = (tn * 4 + tm) >> 1;
+                    if (((tn * 4 + tm) & 1) == 0) gload_lds16(xg[i] + k0, st + i * 1024u);
+                    else gload_lds16(wg[i] + k0, st + kTileU4 * 16 + i * 1024u);
+                    __builtin_amdgcn_sched_barrier(0);
+                    acc[tn][tm] = mfma32<DT>(wfb[tn], xfb[tm], acc[tn][tm]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // drain the tail loads before LDS is released

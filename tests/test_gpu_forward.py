@@ -52,7 +52,7 @@ def test_layernorm(dtype, m_half, d):
 
 @pytest.mark.parametrize("dtype", [zi.FP32, zi.BF16, zi.FP16])
 @pytest.mark.parametrize("m_half,n,k", [(64, 128, 64), (130, 200, 192), (37, 72, 128), (256, 384, 320), (3, 8, 24),
-                                        (2100, 2600, 96), (1024, 8200, 32)])
+                                        (2100, 2600, 128), (1024, 8200, 64)])
 @pytest.mark.parametrize("epi", [0, 1, 2, 3])
 def test_linear_pm(dtype, m_half, n, k, epi):
     """Shapes span several 128-wide tiles with ragged tails; (3, 8, 24) is below the MFMA tile depth; the last
