@@ -1,0 +1,104 @@
+"""GPU parity, part 3: the block-streamed model (Alg. 2's deferred update under Alg. 3's upload /
+compute / offload overlap) must give exactly what the resident model gives, and what the oracle's
+Alg. 2 runner gives."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_03211_amd as zo_amd
+import zo_inputs as zi
+from oracle import zo_oracle as zo
+from gpu_util import DEV, Model
+
+pytestmark = pytest.mark.gpu
+
+SHAPE = dict(n_layers=3, d_model=128, n_heads=2, d_ffn=256, vocab=512, max_pos=64)
+
+
+def _pair(dtype, lr_std=0.05):
+    kw = dict(dtype=dtype, batch=2, seq=40, seed=3, plain_small=False, std=lr_std)
+    return Model(**SHAPE, **kw), Model(**SHAPE, streamed=True, **kw)
+
+
+@pytest.mark.parametrize("dtype,lr", [(zi.BF16, 3e-2), (zi.FP16, 3e-3), (zi.FP32, 1e-3)])
+def test_streamed_equals_resident_bit_for_bit(dtype, lr):
+    res, stm = _pair(dtype)
+    tok, tok_dev = res.tokens()
+    for seed in (0, 1, 2, 3):
+        a = zo_amd.zo_step(res.handle, tok_dev, 2, 40, seed, 1e-3, lr)
+        b = zo_amd.zo_step(stm.handle, tok_dev, 2, 40, seed, 1e-3, lr)
+        assert a == b, (seed, a, b)                         # same kernels, same order per element: same bits
+    th_res = res.theta()
+    before_flush = stm.theta()
+    assert any(x.tobytes() != y.tobytes() for x, y in zip(th_res, before_flush))      # last update still pending
+    zo_amd.zo_flush_pending(stm.handle)
+    zo_amd.zo_flush_pending(stm.handle)                     # second flush is a no-op
+    assert all(x.tobytes() == y.tobytes() for x, y in zip(th_res, stm.theta()))
+    assert any(x.tobytes() != y.tobytes() for x, y in zip(th_res, res.theta0))        # and the steps did move theta
+    res.close(); stm.close()
+
+
+def test_streamed_matches_the_oracles_alg2_runner():
+    stm = Model(**SHAPE, dtype=zi.FP32, batch=2, seq=40, seed=4, plain_small=False, std=0.05, streamed=True)
+    tok, tok_dev = stm.tokens()
+    theta = [t.copy() for t in stm.theta0]
+    runner = zo.Alg2Runner(stm.ocfg, theta, 1e-3, 1e-3, literal=False)
+    for seed in (5, 6, 7):
+        lp, lm, g = zo_amd.zo_step(stm.handle, tok_dev, 2, 40, seed, 1e-3, 1e-3)
+        olp, olm, og = runner.step(tok, seed)
+        assert abs(lp / olp - 1) < 1e-10 and abs(lm / olm - 1) < 1e-10
+        assert abs(g / og - 1) < 1e-5
+    zo_amd.zo_flush_pending(stm.handle)
+    runner.flush()
+    for a, b in zip(stm.theta(), theta):
+        assert np.all(np.abs(a.astype(np.float64) - b) <= 1e-5 * np.abs(b) + 1e-10)
+    stm.close()
+
+
+def test_manual_schedule_equals_zo_step_and_state_errors():
+    a = Model(**SHAPE, dtype=zi.BF16, batch=2, seq=40, seed=3, plain_small=False, std=0.05, streamed=True)
+    b = Model(**SHAPE, dtype=zi.BF16, batch=2, seq=40, seed=3, plain_small=False, std=0.05, streamed=True)
+    tok, tok_dev = a.tokens()
+    P, C, W = zo_amd.ZO_PHASE_PREFETCH, zo_amd.ZO_PHASE_COMPUTE, zo_amd.ZO_PHASE_WRITEBACK
+    L = SHAPE["n_layers"]
+    for seed in (0, 1):
+        want = zo_amd.zo_step(a.handle, tok_dev, 2, 40, seed, 1e-3, 3e-2)
+        zo_amd.zo_stream_begin(b.handle, tok_dev, 2, 40, seed, 1e-3)
+        zo_amd.zo_stream_block(b.handle, 0, P)
+        for l in range(L):                                   # Alg. 3: U(W_{l+1}) with C(W_l), then O(W_l)
+            if l + 1 < L:
+                zo_amd.zo_stream_block(b.handle, l + 1, P)
+            zo_amd.zo_stream_block(b.handle, l, C | W)
+        got = zo_amd.zo_stream_end(b.handle, 3e-2)
+        assert got == want
+    zo_amd.zo_flush_pending(a.handle); zo_amd.zo_flush_pending(b.handle)
+    assert all(x.tobytes() == y.tobytes() for x, y in zip(a.theta(), b.theta()))
+
+    def status(fn, *args):
+        with pytest.raises(zo_amd.ZoError) as e:
+            fn(*args)
+        return e.value.status
+
+    zo_amd.zo_step(b.handle, tok_dev, 2, 40, 8, 1e-3, 3e-2)                                # leaves an update pending
+    assert status(zo_amd.zo_stream_block, b.handle, 0, C) == zo_amd.ZO_ESTATE              # no step open
+    assert status(zo_amd.zo_dual_forward, b.handle, tok_dev, 2, 40, 0, 1e-3) == zo_amd.ZO_ESTATE
+    assert status(zo_amd.zo_perturb, b.handle, 0, 1e-3, 2, 1) == zo_amd.ZO_ESTATE          # a host-resident tensor
+    zo_amd.zo_perturb(b.handle, 0, 0.0, 0, 2)                                              # device-resident ones are fine
+    zo_amd.zo_stream_begin(b.handle, tok_dev, 2, 40, 9, 1e-3)
+    assert status(zo_amd.zo_stream_begin, b.handle, tok_dev, 2, 40, 9, 1e-3) == zo_amd.ZO_ESTATE   # already open
+    assert status(zo_amd.zo_stream_block, b.handle, 0, C) == zo_amd.ZO_ESTATE              # not prefetched
+    zo_amd.zo_stream_block(b.handle, 0, P)
+    assert status(zo_amd.zo_stream_block, b.handle, 2, P) == zo_amd.ZO_ESTATE              # slot 0 still awaits COMPUTE
+    zo_amd.zo_stream_block(b.handle, 1, P)
+    assert status(zo_amd.zo_stream_block, b.handle, 1, C) == zo_amd.ZO_ESTATE              # out of order
+    assert status(zo_amd.zo_stream_end, b.handle, 1e-3) == zo_amd.ZO_ESTATE                # blocks missing
+    assert status(zo_amd.zo_stream_block, b.handle, 7, P) == zo_amd.ZO_EINVAL
+    zo_amd.zo_stream_block(b.handle, 0, C)
+    assert status(zo_amd.zo_stream_block, b.handle, 2, P) == zo_amd.ZO_ESTATE              # block 0 updated, not written back
+    zo_amd.zo_stream_block(b.handle, 0, W)
+    zo_amd.zo_stream_block(b.handle, 2, P)
+    zo_amd.zo_stream_block(b.handle, 1, C | W)
+    zo_amd.zo_stream_block(b.handle, 2, C | W)
+    lp, lm, g = zo_amd.zo_stream_end(b.handle, 1e-3)
+    assert np.isfinite(g)
+    a.close(); b.close()
