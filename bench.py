@@ -26,7 +26,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="opt-13b", help="tiny | opt-125m | opt-1.3b | opt-13b")
+    ap.add_argument("--config", default="opt-13b", help="tiny | opt-125m | opt-1.3b | opt-13b | opt-175b (streamed)")
+    ap.add_argument("--host-blocks", type=int, default=6,
+                    help="streamed configs: number of distinct real-shape pinned host blocks; the layers cycle through them "
+                         "(the full 175B model needs 348 GB of pinned memory, more than a box may pin)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy, a kernel of known HBM traffic that calibrates "
@@ -135,15 +138,42 @@ def main():
     c = zi.CONFIGS[args.config]
     dev = "cuda:0"
     shapes = zi.tensor_shapes(c["n_layers"], c["d_model"], c["d_ffn"], c["vocab"], c["max_pos"])
-    tensors = device_weights(torch, shapes, c["dtype"], dev)
+    streamed = args.config == "opt-175b"
+    host_ring = None
+    if not streamed:
+        tensors = device_weights(torch, shapes, c["dtype"], dev)
+    else:
+        # embeddings and final LayerNorm on the device; blocks in pinned host memory, one contiguous region each
+        tdt = {0: torch.float32, 1: torch.bfloat16, 2: torch.float16}[c["dtype"]]
+        resident = device_weights(torch, shapes[:2] + shapes[-2:], c["dtype"], dev)
+        block_shapes = shapes[2:18]
+        per_block = sum(int(torch.Size(sh).numel()) for _, sh in block_shapes)
+        nring = max(1, min(args.host_blocks, c["n_layers"]))
+        host_ring = torch.empty((nring, per_block), dtype=tdt, pin_memory=True)
+        one = torch.cat([t.reshape(-1) for t in device_weights(torch, block_shapes, c["dtype"], dev, seed=7)]).cpu()
+        for r in range(nring):
+            host_ring[r].copy_(one)
+        del one
+        offs, o = [], 0
+        for _, sh in block_shapes:
+            offs.append(o)
+            o += int(torch.Size(sh).numel())
+        esz = host_ring.element_size()
+        tensors = [resident[0], resident[1]]
+        for l in range(c["n_layers"]):
+            base = host_ring.data_ptr() + (l % nring) * per_block * esz
+            tensors += [base + off * esz for off in offs]
+        tensors += [resident[2], resident[3]]
     tokens = torch.randint(0, c["vocab"], (c["batch"], c["seq"]), dtype=torch.int32, device=dev,
                            generator=torch.Generator(device=dev).manual_seed(1))
-    cfg = zo_amd.make_config(c["n_layers"], c["d_model"], c["n_heads"], c["d_ffn"], c["vocab"], c["max_pos"], c["dtype"])
+    cfg = zo_amd.make_config(c["n_layers"], c["d_model"], c["n_heads"], c["d_ffn"], c["vocab"], c["max_pos"], c["dtype"],
+                             zo_amd.ZO_STREAMED if streamed else zo_amd.ZO_RESIDENT)
     nbytes = zo_amd.zo_workspace_bytes(cfg, c["batch"], c["seq"])
     ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     stream = torch.cuda.Stream(device=dev)
+    copy_stream = torch.cuda.Stream(device=dev) if streamed else None
     torch.cuda.synchronize()
-    h = zo_amd.zo_init_model(cfg, tensors, ws, nbytes, c["batch"], c["seq"], stream, None)
+    h = zo_amd.zo_init_model(cfg, tensors, ws, nbytes, c["batch"], c["seq"], stream, copy_stream)
 
     def step(i):
         zo_amd.zo_step(h, tokens, c["batch"], c["seq"], i, c["eps"], c["lr"], zo_amd.ZO_MODE_FUSED, want_host=False)
@@ -211,11 +241,20 @@ def main():
         "dtype": dname, "data": "synthetic",
         "config": {"workload": args.config, "n_layers": c["n_layers"], "d_model": c["d_model"], "n_heads": c["n_heads"],
                    "d_ffn": c["d_ffn"], "vocab": c["vocab"], "batch": c["batch"], "seq_len": c["seq"], "eps": c["eps"],
-                   "lr": c["lr"], "mode": "fused", "residency": "hbm"},
+                   "lr": c["lr"], "mode": "fused", "residency": "pinned-host blocks, streamed" if streamed else "hbm"},
         "roofline": roof,
         "kernels": kernels,
         "last_step": {"l_plus": lp, "l_minus": lm, "g": g, "device_flags": flags},
     }
+    if streamed:
+        block_bytes = host_ring.shape[1] * host_ring.element_size()
+        step_s = dt / args.steps
+        out["streaming"] = {"block_bytes": block_bytes, "blocks_per_step": c["n_layers"], "distinct_host_blocks": int(host_ring.shape[0]),
+                            "h2d_gbs": block_bytes * c["n_layers"] / step_s / 1e9,
+                            "d2h_gbs": block_bytes * c["n_layers"] / step_s / 1e9 if args.warmup + args.steps > 1 else 0.0,
+                            "compute_ms_per_block": sum(v["ms_per_step"] for v in kernels.values()) / c["n_layers"],
+                            "note": "layers cycle through the distinct host blocks, so values are not those of one model; "
+                                    "traffic, kernels and schedule are those of the full model"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(c, args.config)
     print(json.dumps(out))
