@@ -1,0 +1,104 @@
+"""GPU parity at the full sizes bench.py times (OPT-13B shapes, batch 4 x seq 2048, bf16), in the same
+launch configuration, on sampled outputs the oracle computes one by one.  Inputs are drawn on the device
+by torch's generator (a seeded library generator, not the HIP path) and the sampled rows / columns are
+copied back for the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_03211_amd as zo_amd
+import zo_inputs as zi
+from oracle import zo_oracle as zo
+from gpu_util import DEV, to_host
+
+pytestmark = pytest.mark.gpu
+
+D, F, H, DH, V = 5120, 20480, 40, 128, 50272
+M_HALF = 4 * 2048
+BF = zi.BF16
+
+
+def _gen(seed):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    return g
+
+
+def _wide(t):
+    """bf16 device tensor (any shape) -> fp64 numpy."""
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("n,k,epi", [(3 * D, D, 0), (F, D, 1), (D, F, 2), (D, D, 2)])
+def test_linear_at_13b_shapes_sampled(n, k, epi):
+    g = _gen(n + k + epi)
+    x = torch.randn(2 * M_HALF, k, device=DEV, generator=g).to(torch.bfloat16)
+    w = [(0.02 * torch.randn(n, k, device=DEV, generator=g)).to(torch.bfloat16) for _ in range(2)]
+    b = [(0.1 * torch.randn(n, device=DEV, generator=g)).to(torch.bfloat16) for _ in range(2)]
+    if epi == 2:
+        y = torch.randn(2 * M_HALF, n, device=DEV, generator=g)
+        y0 = y.clone()
+    else:
+        y = torch.zeros(2 * M_HALF, n, device=DEV, dtype=torch.bfloat16)
+    zo_amd.zo_kernel_linear_pm(x, w[0], w[1], b[0], b[1], y, BF, M_HALF, n, k, epi)
+    rng = np.random.Generator(np.random.PCG64(5))
+    rows = np.concatenate([rng.integers(0, 2 * M_HALF, 24), [0, M_HALF - 1, M_HALF, 2 * M_HALF - 1]])
+    cols = np.concatenate([rng.integers(0, n, 24), [0, n - 1, 255, 256]])
+    for r in rows:
+        s = int(r >= M_HALF)
+        xr = _wide(x[int(r)])
+        want = _wide(w[s][cols]) @ xr + _wide(b[s][cols])
+        if epi == 1:
+            want = np.maximum(want, 0)
+        if epi == 2:
+            want = want + y0[int(r)][cols].double().cpu().numpy()
+        got = y[int(r)][cols].double().cpu().numpy()
+        scale = np.sqrt(k) * 0.02 + 1.0
+        tol = (2.0**-8 if epi != 2 else 1e-4) * scale * 2
+        assert np.max(np.abs(got - want)) < tol, (r, np.max(np.abs(got - want)), tol)
+
+
+def test_attention_at_13b_shape_sampled_heads():
+    n_seq, seq = 8, 2048
+    g = _gen(11)
+    qkv = torch.randn(n_seq * seq, 3 * D, device=DEV, generator=g).to(torch.bfloat16)
+    out = torch.zeros(n_seq * seq, D, device=DEV, dtype=torch.bfloat16)
+    zo_amd.zo_kernel_attention(qkv, out, BF, n_seq, seq, H, DH)
+    for sq, head in [(0, 0), (3, 17), (7, 39)]:
+        blk = qkv[sq * seq:(sq + 1) * seq]
+        q, k, v = (_wide(blk[:, o * D + head * DH:o * D + (head + 1) * DH])[None] for o in range(3))
+        want = zo.causal_attention(q, k, v, 1)[0]
+        got = _wide(out[sq * seq:(sq + 1) * seq, head * DH:(head + 1) * DH])
+        assert np.max(np.abs(got - want)) < 3 * 2.0**-8 * (1 + np.abs(want).max())
+
+
+def test_layernorm_and_update_streams_at_13b_sizes_sampled():
+    g = _gen(12)
+    h = torch.randn(2 * M_HALF, D, device=DEV, generator=g) * 2 + 0.3
+    gam = [(1 + 0.1 * torch.randn(D, device=DEV, generator=g)).to(torch.bfloat16) for _ in range(2)]
+    bet = [(0.1 * torch.randn(D, device=DEV, generator=g)).to(torch.bfloat16) for _ in range(2)]
+    y = torch.empty(2 * M_HALF, D, device=DEV, dtype=torch.bfloat16)
+    zo_amd.zo_kernel_layernorm_pm(h, gam[0], gam[1], bet[0], bet[1], y, BF, M_HALF, D, 1e-5)
+    for r in (0, 4097, M_HALF - 1, M_HALF, 2 * M_HALF - 1):
+        s = int(r >= M_HALF)
+        want = zo.layer_norm(h[r].double().cpu().numpy(), _wide(gam[s]), _wide(bet[s]), 1e-5)
+        assert np.max(np.abs(_wide(y[r]) - want) / (np.abs(want) + 1)) < 1.5 * 2.0**-8
+    # one FFN matrix of a 13B block through the in-place stream and through staging: sampled elements, bit-exact
+    n = D * F
+    theta = (0.02 * torch.randn(n, device=DEV, generator=g)).to(torch.bfloat16)
+    keep = theta.clone()
+    zo_amd.zo_kernel_axpy_z(theta, theta, BF, n, 2**40 + 3, 654, -2e-3)
+    wp, wm = torch.empty_like(theta), torch.empty_like(theta)
+    zo_amd.zo_kernel_stage_pm(keep, wp, wm, BF, D, F, 1, 99, 654, 1e-3)
+    rng = np.random.Generator(np.random.PCG64(6))
+    idx = np.unique(np.concatenate([rng.integers(0, n, 4000), [0, 1, 2, 3, n - 4, n - 1, 4095, 4096]]))
+    src = to_host(keep[torch.from_numpy(idx).to(DEV)], BF)
+    got = to_host(theta[torch.from_numpy(idx).to(DEV)], BF)
+    tr = (idx % F) * D + idx // F                               # where element (r, c) lands after transposition
+    got_p = to_host(wp[torch.from_numpy(tr).to(DEV)], BF)
+    got_m = to_host(wm[torch.from_numpy(tr).to(DEV)], BF)
+    for j, i in enumerate(idx):
+        one = src[j:j + 1]
+        assert zo.axpy_z(one, BF, 2**40 + 3, 654, -2e-3, first=int(i))[0] == got[j]
+        assert zo.axpy_z(one, BF, 99, 654, 1e-3, first=int(i))[0] == got_p[j]
+        assert zo.axpy_z(one, BF, 99, 654, -np.float32(1e-3), first=int(i))[0] == got_m[j]
