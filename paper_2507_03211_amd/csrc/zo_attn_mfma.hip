@@ -10,7 +10,8 @@
 // so the online-softmax running maximum, normaliser and the rescaling of O are per-lane
 // scalars, and the row reductions need one cross-half shuffle.  The contraction order of the
 // P V product follows the accumulator layout of S^T (keys 16s + 4h + {0..3}, 16s + 8 + 4h +
-// {0..3} for lane half h), which V^T is read with as well, so P never leaves registers.
+// {0..3} for lane half h), which V^T is read with as well, so P never leaves registers.  V stays
+// row-major in LDS; its transposed fragments come from the LDS transposing read of gfx950.
 #include "zo_kernels.h"
 #include "zo_types.hip.h"
 
@@ -37,16 +38,22 @@ template <int DT> __device__ __forceinline__ uint32_t pack2(float a, float b)
     return (uint32_t)Prec<DT>::acc2a(a) | ((uint32_t)Prec<DT>::acc2a(b) << 16);
 }
 
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers across the loop
+
 template <int DT, int DH>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restrict__ qkv, uint16_t *__restrict__ out, int seq,
                                                         int n_heads)
 {
-    constexpr int CH = DH / 8;            // 16-byte chunks per K row
-    constexpr int VLD = BKV + 4;          // padded V^T row: 34 banks, so 32 lanes reading 8 bytes each spread over all 64
-    __shared__ uint4 ks[BKV * CH];        // K tile, chunk c of key r at c ^ kswz(r): 16 rows -> 16 distinct bank groups
-    __shared__ __attribute__((aligned(16))) uint16_t vt[DH * VLD];   // V^T tile: [channel][key]
-
+    constexpr int CH = DH / 8;            // 16-byte chunks per K / V row
+    // K and V tiles, both [key][channel] as they sit in memory, 16-byte chunks XOR-swizzled per key so that
+    // the MFMA fragment reads of K (32 keys, one chunk) and the transposing reads of V (4 keys x 32 bytes
+    // per 16 lanes) are free of conflicts on the 64-bank LDS.
+    __shared__ u32x4 ks[BKV * CH];
+    __shared__ u32x4 vs[BKV * CH];
     auto kswz = [](int r) { return DH == 128 ? (r & 15) : ((r >> 1) & 7); };
+    auto vswz = [](int r) { return DH == 128 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); };
+
     const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;             // long rows first
     const int head = blockIdx.y, sq = blockIdx.z;
     const int d = n_heads * DH, ld = 3 * d;
@@ -67,46 +74,52 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
     for (int c = 0; c < DH / 32; ++c)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[c][i] = 0.0f;
+    // running maximum of the raw scores, and the same times log2(e)/sqrt(d_head) (the exponent's offset)
     float m_run = -INFINITY, l_run = 0.0f;
-    const float sc = 1.4426950408889634f / __builtin_sqrtf((float)DH);    // log2(e) / sqrt(d_head)
+    const float sc = 1.4426950408889634f / __builtin_sqrtf((float)DH);
 
-    // global -> LDS assignment for a K/V tile: key = tid % 64, chunks tid / 64 + 4 i
-    const int lkey = tid & 63, lch = tid >> 6;
-    constexpr int NLD = CH / 4;
-    uint4 kreg[NLD], vreg[NLD];
-    auto load_tile = [&](int k0) {
-        int kr = k0 + lkey; kr = kr < seq ? kr : seq - 1;
-        const uint16_t *kp = base + (size_t)kr * ld + d;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            kreg[i] = *(const uint4 *)(kp + (lch + 4 * i) * 8);
-            vreg[i] = *(const uint4 *)(kp + d + (lch + 4 * i) * 8);
-        }
-    };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int c = lch + 4 * i;
-            ks[lkey * CH + (c ^ kswz(lkey))] = kreg[i];
-            const uint32_t w[4] = {vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                vt[(c * 8 + 2 * e) * VLD + lkey] = (uint16_t)(w[e] & 0xffffu);
-                vt[(c * 8 + 2 * e + 1) * VLD + lkey] = (uint16_t)(w[e] >> 16);
-            }
-        }
+    // global -> LDS assignment for a K/V tile: consecutive lanes take consecutive 16-byte chunks of one key row
+    // (whole cache lines per wave instruction); 256 threads cover 256 / CH keys per pass
+    constexpr int RPP = 256 / CH;         // key rows per pass
+    constexpr int NLD = BKV / RPP;
+    const int lch = tid % CH, lrow = tid / CH;
+    u32x4 kreg[NLD], vreg[NLD];
+#define ZO_ATTN_LOAD_TILE(K0)                                                        \
+    _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                                \
+        int kr = (K0) + lrow + RPP * i;                                              \
+        kr = kr < seq ? kr : seq - 1;                                                \
+        const uint16_t *kp = base + (size_t)kr * ld + d + lch * 8;                   \
+        kreg[i] = *(const u32x4 *)kp;                                                \
+        vreg[i] = *(const u32x4 *)(kp + d);                                          \
+    }
+    // Transposing LDS read (ds_read_b64_tr_b16): in every group of 16 lanes, lane j hands in the address of
+    // four consecutive 16-bit elements ("row j") and lane i gets back element i%4 of rows i/4, i/4+4, i/4+8,
+    // i/4+12.  With lane j pointing at key kb + j/4, channels cb + 4 (j%4) .. + 3, lane i receives channel
+    // cb + i for the four keys kb .. kb+3: a V^T fragment straight from row-major V.
+    const int tj = lane & 15;
+    const int tr_key = tj >> 2;                                  // + key base
+    const int tr_chan = 16 * ((lane >> 4) & 1) + 4 * (tj & 3);   // + 32 * channel tile
+    auto vt_frag = [&](int kb, int ctile) {
+        const int key = kb + tr_key, chan = ctile * 32 + tr_chan;
+        const uint16_t *p = (const uint16_t *)vs + (size_t)(key * CH + ((chan >> 3) ^ vswz(key))) * 8 + (chan & 7);
+        return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16 *)p);
     };
 
     const int q_hi = qt * BQ + BQ - 1 < seq - 1 ? qt * BQ + BQ - 1 : seq - 1;   // last query row of the workgroup
     const int n_tiles = q_hi / BKV + 1;
-    load_tile(0);
+    ZO_ATTN_LOAD_TILE(0)
     for (int t = 0; t < n_tiles; ++t) {
         const int k0 = t * BKV;
         __syncthreads();                 // previous tile fully consumed
-        store_tile();
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int r = lrow + RPP * i;
+            ks[r * CH + (lch ^ kswz(r))] = kreg[i];
+            vs[r * CH + (lch ^ vswz(r))] = vreg[i];
+        }
         __syncthreads();
-        if (t + 1 < n_tiles) load_tile(k0 + BKV);
-        if (k0 > q0 + 31) continue;      // tile entirely in this wave's future (uniform per wave)
+        ZO_ATTN_LOAD_TILE(t + 1 < n_tiles ? k0 + BKV : k0)   // prefetch (the last one reloads its own tile, unused)
+        if (k0 <= q0 + 31) {             // else: tile entirely in this wave's future (uniform per wave)
 
         // S^T tile: 64 keys x 32 queries = two 32 x 32 accumulators
         f32x16 sacc[2];
@@ -117,46 +130,51 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
 #pragma unroll
             for (int s = 0; s < DH / 16; ++s) {
                 const int r = kt * 32 + fr;
-                const uint4 kf = ks[r * CH + ((2 * s + fh) ^ kswz(r))];
-                sacc[kt] = mfma32<DT>(kf, qf[s], sacc[kt]);
+                const u32x4 kf = ks[r * CH + ((2 * s + fh) ^ kswz(r))];
+                sacc[kt] = mfma32<DT>(__builtin_bit_cast(uint4, kf), qf[s], sacc[kt]);
             }
         }
-        // scale, mask (key > query), tile maximum
-        const bool diag = k0 + BKV - 1 > q0;
-        float tmax = -INFINITY;
+        // mask (key > query) on the diagonal tiles, tile maximum of the raw scores
+        if (k0 + BKV - 1 > q0) {
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int key = k0 + kt * 32 + 8 * (i >> 2) + 4 * fh + (i & 3);
+                    if (key > qrow) sacc[kt][i] = -INFINITY;
+                }
+        }
+        float tmax = sacc[0][0];
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float v = sacc[kt][i] * sc;
-                if (diag) {
-                    const int key = k0 + kt * 32 + 8 * (i >> 2) + 4 * fh + (i & 3);
-                    if (key > qrow) v = -INFINITY;
-                }
-                sacc[kt][i] = v;
-                tmax = v > tmax ? v : tmax;
-            }
+            for (int i = 0; i < 16; ++i) tmax = sacc[kt][i] > tmax ? sacc[kt][i] : tmax;
         const float other = __shfl_xor(tmax, 32, 64);
         tmax = other > tmax ? other : tmax;
         const float m_new = tmax > m_run ? tmax : m_run;      // finite: key k0 <= q0 <= qrow is never masked
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
+        const float moff = -m_new * sc;
         float psum = 0.0f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(sacc[kt][i] - m_new);
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt][i], sc, moff));
                 sacc[kt][i] = p;
                 psum += p;
             }
         psum += __shfl_xor(psum, 32, 64);
         l_run = l_run * alpha + psum;
+        // rescale O only when some row's maximum moved (rare after the first tiles)
+        if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+#pragma unroll
+            for (int c = 0; c < DH / 32; ++c)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[c][i] *= alpha;
+        }
         m_run = m_new;
-#pragma unroll
-        for (int c = 0; c < DH / 32; ++c)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[c][i] *= alpha;
-        // O^T += V^T P^T : four contraction steps of 16 keys
+        // O^T += V^T P^T : four contraction steps of 16 keys; lane half h contracts keys 16 s + 4 h + {0..3}
+        // and 16 s + 8 + 4 h + {0..3}, the order in which the S^T accumulators hold them
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int kt = s >> 1, rb = (s & 1) * 8;
@@ -165,14 +183,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
             pf.y = pack2<DT>(sacc[kt][rb + 2], sacc[kt][rb + 3]);
             pf.z = pack2<DT>(sacc[kt][rb + 4], sacc[kt][rb + 5]);
             pf.w = pack2<DT>(sacc[kt][rb + 6], sacc[kt][rb + 7]);
-            const int key_a = 16 * s + 4 * fh;       // keys key_a .. +3 and key_a + 8 .. +3
+            const int key_a = 16 * s + 4 * fh;
 #pragma unroll
             for (int c = 0; c < DH / 32; ++c) {
-                const uint16_t *vrow = vt + (c * 32 + fr) * VLD;
-                const uint2 lo = *(const uint2 *)(vrow + key_a);
-                const uint2 hi = *(const uint2 *)(vrow + key_a + 8);
-                oacc[c] = mfma32<DT>(uint4{lo.x, lo.y, hi.x, hi.y}, pf, oacc[c]);
+                const v4i16 lo = vt_frag(key_a, c), hi = vt_frag(key_a + 8, c);
+                const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
+                oacc[c] = mfma32<DT>(uint4{lo2.x, lo2.y, hi2.x, hi2.y}, pf, oacc[c]);
             }
+        }
         }
     }
 
@@ -190,6 +208,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
             }
     }
 }
+
+#undef ZO_ATTN_LOAD_TILE
 
 }  // namespace
 

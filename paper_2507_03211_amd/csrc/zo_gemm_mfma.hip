@@ -28,6 +28,7 @@ namespace zo {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: arrays of it stay in registers
 
 namespace {
 
@@ -85,8 +86,8 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__rest
                                                           const uint16_t *__restrict__ b_m, void *__restrict__ y,
                                                           int m_half, int n, int k)
 {
-    __shared__ uint4 xs[2][BM * kChunksPerRow];
-    __shared__ uint4 ws[2][BN * kChunksPerRow];
+    __shared__ u32x4 xs[2][BM * kChunksPerRow];
+    __shared__ u32x4 ws[2][BN * kChunksPerRow];
     const int sign = blockIdx.z;
     const uint16_t *xa = x + (size_t)sign * m_half * k;
     const uint16_t *wt = sign ? wt_m : wt_p;
@@ -105,12 +106,12 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__rest
         xg[i] = xa + (size_t)xr * k + lc * 8;
         wg[i] = wt + (size_t)wr * k + lc * 8;
     }
-    uint4 xreg[4], wreg[4];
+    u32x4 xreg[4], wreg[4];
     auto load_global = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            xreg[i] = *(const uint4 *)(xg[i] + k0);
-            wreg[i] = *(const uint4 *)(wg[i] + k0);
+            xreg[i] = *(const u32x4 *)(xg[i] + k0);
+            wreg[i] = *(const u32x4 *)(wg[i] + k0);
         }
     };
     auto store_lds = [&](int buf) {
@@ -142,8 +143,8 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__rest
             uint4 wf[2], xf[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                wf[t] = ws[buf][lds_slot(wn * 64 + t * 32 + fr, ks * 2 + fh)];
-                xf[t] = xs[buf][lds_slot(wm * 64 + t * 32 + fr, ks * 2 + fh)];
+                wf[t] = __builtin_bit_cast(uint4, ws[buf][lds_slot(wn * 64 + t * 32 + fr, ks * 2 + fh)]);
+                xf[t] = __builtin_bit_cast(uint4, xs[buf][lds_slot(wm * 64 + t * 32 + fr, ks * 2 + fh)]);
             }
 #pragma unroll
             for (int tn = 0; tn < 2; ++tn)

@@ -11,10 +11,10 @@ constexpr int kFP32 = 0, kBF16 = 1, kFP16 = 2;
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
 {
-    uint32_t x = __float_as_uint(f);
-    if ((x & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x >> 16) | 0x0040u);
-    x += 0x7fffu + ((x >> 16) & 1u);
-    return (uint16_t)(x >> 16);
+    __bf16 b = (__bf16)f;      // v_cvt_pk_bf16_f32 on gfx950: nearest even
+    uint16_t h;
+    __builtin_memcpy(&h, &b, 2);
+    return h;
 }
 __device__ __forceinline__ float f16_bits_to_f32(uint16_t h)
 {
