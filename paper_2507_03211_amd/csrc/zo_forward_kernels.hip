@@ -74,6 +74,60 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const void *resid, const
     }
 }
 
+
+// Fast path for 2-byte activations: one wavefront per row, the row held in registers (NV float4 per lane),
+// so the residual stream is read once; statistics by wavefront shuffles only.  d % 4 == 0.
+template <int DT, int NV>
+__global__ __launch_bounds__(256) void layernorm_wave_kernel(const float *__restrict__ resid, const uint16_t *__restrict__ g_p,
+                                                             const uint16_t *__restrict__ g_m, const uint16_t *__restrict__ b_p,
+                                                             const uint16_t *__restrict__ b_m, uint16_t *__restrict__ y, int rows,
+                                                             int m_half, int d, float eps)
+{
+    using P = Prec<DT>;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= rows) return;
+    const int sign = row / m_half;
+    const float4 *h = (const float4 *)(resid + (size_t)row * d);
+    const uint2 *g = (const uint2 *)(sign ? g_m : g_p), *b = (const uint2 *)(sign ? b_m : b_p);
+    uint2 *out = (uint2 *)(y + (size_t)row * d);
+    const int nvec = d >> 2;
+    float4 v[NV];
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + 64 * i;
+        v[i] = c < nvec ? h[c] : float4{0.0f, 0.0f, 0.0f, 0.0f};
+        s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        if (lane + 64 * i < nvec) {
+            const float a = v[i].x - mean, bb = v[i].y - mean, c = v[i].z - mean, dd = v[i].w - mean;
+            q += (a * a + bb * bb) + (c * c + dd * dd);
+        }
+    }
+    const float rstd = 1.0f / __builtin_sqrtf(wave_sum(q) / (float)d + eps);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nvec) {
+            const uint2 gr = g[c], br = b[c];
+            const float g0 = P::w2f((uint16_t)(gr.x & 0xffff)), g1 = P::w2f((uint16_t)(gr.x >> 16));
+            const float g2 = P::w2f((uint16_t)(gr.y & 0xffff)), g3 = P::w2f((uint16_t)(gr.y >> 16));
+            const float b0 = P::w2f((uint16_t)(br.x & 0xffff)), b1 = P::w2f((uint16_t)(br.x >> 16));
+            const float b2 = P::w2f((uint16_t)(br.y & 0xffff)), b3 = P::w2f((uint16_t)(br.y >> 16));
+            const float o0 = (v[i].x - mean) * rstd * g0 + b0, o1 = (v[i].y - mean) * rstd * g1 + b1;
+            const float o2 = (v[i].z - mean) * rstd * g2 + b2, o3 = (v[i].w - mean) * rstd * g3 + b3;
+            uint2 o;
+            o.x = (uint32_t)P::acc2a(o0) | ((uint32_t)P::acc2a(o1) << 16);
+            o.y = (uint32_t)P::acc2a(o2) | ((uint32_t)P::acc2a(o3) << 16);
+            out[c] = o;
+        }
+    }
+}
+
 // ------------------------------------------------------------------ plain linear layer
 // y[row, n] = sum_k x[row, k] wt[n, k] (+ bias).  64 x 64 output tile, 16-deep LDS slabs,
 // 4 x 4 outputs per thread.  blockIdx.z selects the sign.
@@ -249,7 +303,24 @@ hipError_t launch_embed(const int32_t *tokens, const void *e_p, const void *e_m,
 hipError_t launch_layernorm(const void *resid, const void *g_p, const void *g_m, const void *b_p, const void *b_m,
                             void *y, int dtype, int n_sign, int m_half, int d, float eps, hipStream_t s)
 {
-    const dim3 grid(n_sign * m_half), block(256);
+    const int rows = n_sign * m_half;
+    if (dtype != kFP32 && d % 4 == 0 && d <= 12288) {
+        const dim3 wgrid((rows + 3) / 4), wblock(256);
+#define ZO_LNW(DT, NV)                                                                                                        \
+    layernorm_wave_kernel<DT, NV><<<wgrid, wblock, 0, s>>>((const float *)resid, (const uint16_t *)g_p, (const uint16_t *)g_m, \
+                                                           (const uint16_t *)b_p, (const uint16_t *)b_m, (uint16_t *)y, rows,   \
+                                                           m_half, d, eps)
+#define ZO_LNW_D(DT)                          \
+    if (d <= 1024) ZO_LNW(DT, 4);             \
+    else if (d <= 2048) ZO_LNW(DT, 8);        \
+    else if (d <= 5120) ZO_LNW(DT, 20);       \
+    else ZO_LNW(DT, 48);
+        if (dtype == kBF16) { ZO_LNW_D(kBF16) } else { ZO_LNW_D(kFP16) }
+#undef ZO_LNW_D
+#undef ZO_LNW
+        return hipGetLastError();
+    }
+    const dim3 grid(rows), block(256);
     ZO_DISPATCH_DT(dtype, (layernorm_kernel<DT><<<grid, block, 0, s>>>(resid, g_p, g_m, b_p, b_m, y, m_half, d, eps)));
     return hipGetLastError();
 }
