@@ -102,6 +102,16 @@ int check_cfg(const zo_config *c)
     return ZO_OK;
 }
 
+// Bytes the LM head needs in its scratch region: a chunk of fp32 (fp64) logits, or the fused path's
+// (max, sum-exp) pairs and target logits for all rows, whichever is larger.
+size_t lmhead_region_bytes(int dtype, size_t rows, int vocab)
+{
+    const size_t lr = rows < 2048 ? rows : 2048;
+    const size_t chunk = lr * (size_t)vocab * acc_bytes(dtype);
+    const size_t fused = rows * ((size_t)(2 * ((vocab + 127) / 128)) * 8 + 4) + 256;
+    return chunk > fused ? chunk : fused;
+}
+
 Workspace plan_workspace(const zo_config &c, int batch, int seq)
 {
     Workspace w{};
@@ -118,7 +128,7 @@ Workspace plan_workspace(const zo_config &c, int batch, int seq)
     w.mid = take(rows * f * ab);
     size_t lr = rows < 2048 ? rows : 2048;       // logits are produced and reduced in row chunks
     w.logits_rows = (int)lr;
-    w.logits = take(lr * (size_t)c.vocab * cb);
+    w.logits = take(lmhead_region_bytes(c.dtype, rows, c.vocab));
     for (int s = 0; s < 2; ++s) w.stage[s] = take(L.total * e);
     for (int s = 0; s < 2; ++s) w.e_pm[s] = take((size_t)c.vocab * d * e);
     for (int s = 0; s < 2; ++s) w.pos_pm[s] = take((size_t)c.max_pos * d * e);
@@ -315,6 +325,20 @@ int lmhead_ce(zo_model *prof, hipStream_t s, const void *x, const void *e_p, con
               void *logits, int logits_rows, int dtype, int n_sign, int m_half, int d, int vocab, bool use_mfma)
 {
     const size_t ab = act_bytes(dtype);
+    if (use_mfma && dtype != kFP32 && mfma_linear_supported(m_half, vocab, d)) {
+        // fused: one sign-batched launch over all rows, no logits in memory
+        const int rows = n_sign * m_half, np = mfma_ce_partials(n_sign, m_half, vocab, d);
+        float *tlogit = (float *)((char *)logits + align_up((size_t)rows * np * 8));
+        const double flops = 2.0 * rows * (double)vocab * d;
+        if (prof) {
+            ZO_PROF(prof, K_LINEAR, flops, launch_linear_mfma(x, e_p, e_m, target, tlogit, logits, dtype, n_sign, m_half, vocab, d, 4, s));
+            ZO_PROF(prof, K_CE, (double)rows * np * 8, launch_ce_finish(logits, np, tlogit, target, row_loss, rows, s));
+        } else {
+            ZO_HIP(launch_linear_mfma(x, e_p, e_m, target, tlogit, logits, dtype, n_sign, m_half, vocab, d, 4, s));
+            ZO_HIP(launch_ce_finish(logits, np, tlogit, target, row_loss, rows, s));
+        }
+        return ZO_OK;
+    }
     for (int sign = 0; sign < n_sign; ++sign) {
         const void *wt = sign ? e_m : e_p;
         for (int r0 = 0; r0 < m_half; r0 += logits_rows) {
@@ -828,7 +852,7 @@ static int lmhead_rows(int m_half) { return m_half < 2048 ? m_half : 2048; }
 extern "C" size_t zo_kernel_lmhead_scratch_bytes(int dtype, int m_half, int vocab)
 {
     if (dtype < 0 || dtype > 2 || m_half < 1 || vocab < 1) return 0;
-    return (size_t)lmhead_rows(m_half) * vocab * acc_bytes(dtype);
+    return lmhead_region_bytes(dtype, 2 * (size_t)m_half, vocab);
 }
 
 extern "C" int zo_kernel_lmhead_ce(const void *x, const void *e_plus, const void *e_minus, const int32_t *target, double *row_loss,

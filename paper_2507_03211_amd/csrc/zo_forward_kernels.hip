@@ -258,6 +258,27 @@ __global__ __launch_bounds__(256) void ce_rows_kernel(const Acc *__restrict__ lo
     if (threadIdx.x == 0) row_loss[r] = tg >= 0 ? (log(s) + mx - (double)lg[tg]) : (double)__builtin_nan("");
 }
 
+// Merge the (max, sum-exp) pairs the fused LM-head epilogue left for a row: one wavefront per row.
+__global__ __launch_bounds__(256) void ce_finish_kernel(const float2 *__restrict__ partials, int n_partial,
+                                                        const float *__restrict__ target_logit,
+                                                        const int32_t *__restrict__ target, double *__restrict__ row_loss,
+                                                        int rows)
+{
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (r >= rows) return;
+    const int tg = target[r];
+    if (tg == -1) { if (lane == 0) row_loss[r] = 0.0; return; }
+    const float2 *p = partials + (size_t)r * n_partial;
+    float mx = -INFINITY;
+    for (int i = lane; i < n_partial; i += 64) mx = p[i].x > mx ? p[i].x : mx;
+    mx = wave_max(mx);
+    double s = 0.0;
+    for (int i = lane; i < n_partial; i += 64)
+        if (p[i].x > -INFINITY) s += (double)p[i].y * exp((double)p[i].x - (double)mx);
+    s = wave_sum(s);
+    if (lane == 0) row_loss[r] = tg >= 0 ? (log(s) + (double)mx - (double)target_logit[r]) : (double)__builtin_nan("");
+}
+
 // L+- = sum of the sign's row losses / count, in a fixed order (deterministic).
 __global__ __launch_bounds__(1024) void loss_reduce_kernel(const double *__restrict__ row_loss, int m_half, int count,
                                                            double *__restrict__ loss_pm)
@@ -364,6 +385,15 @@ hipError_t launch_ce_rows(const void *logits, const int32_t *target, double *row
     if (rows == 0) return hipSuccess;
     if (dtype == kFP32) ce_rows_kernel<double><<<dim3(rows), dim3(256), 0, s>>>((const double *)logits, target, row_loss, vocab);
     else ce_rows_kernel<float><<<dim3(rows), dim3(256), 0, s>>>((const float *)logits, target, row_loss, vocab);
+    return hipGetLastError();
+}
+
+hipError_t launch_ce_finish(const void *partials, int n_partial, const float *target_logit, const int32_t *target,
+                            double *row_loss, int rows, hipStream_t s)
+{
+    if (rows == 0) return hipSuccess;
+    ce_finish_kernel<<<dim3((rows + 3) / 4), dim3(256), 0, s>>>((const float2 *)partials, n_partial, target_logit, target, row_loss,
+                                                                rows);
     return hipGetLastError();
 }
 

@@ -75,6 +75,41 @@ __device__ __forceinline__ void epilogue_store(float (&v)[4], const uint16_t *__
     }
 }
 
+
+// Epilogue 4 (tied LM head fused with the cross-entropy reduction): nothing of the logits is stored.  A lane
+// holds TN * 16 logits of one row (4 runs of 4 consecutive columns per MFMA tile); it reduces them to a
+// (maximum, sum of exp) pair, merges with the other lane half (the remaining columns of the wave's range)
+// and the wave writes one pair per row and per wave-column-range; the lane that holds the target column
+// stores that logit.  A last small kernel merges the pairs of a row into logsumexp - target logit.
+// Argument reuse for this epilogue: bias_p -> int32 target[rows], bias_m -> float target_logit[rows],
+// y -> float2 partial[rows][n_partial].
+template <int TN>
+__device__ __forceinline__ void ce_partial_row(const f32x16 (&a)[TN], int col0, int fh, int n, int tg, float *tgt_logit_row,
+                                               float2 *partial_slot)
+{
+    float mx = -INFINITY;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int nc = col0 + tn * 32 + 8 * (i >> 2) + 4 * fh + (i & 3);
+            if (nc < n) mx = a[tn][i] > mx ? a[tn][i] : mx;
+        }
+    float sum = 0.0f;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int nc = col0 + tn * 32 + 8 * (i >> 2) + 4 * fh + (i & 3);
+            if (nc < n) sum += __expf(a[tn][i] - mx);
+            if (nc == tg) *tgt_logit_row = a[tn][i];
+        }
+    const float mo = __shfl_xor(mx, 32, 64), so = __shfl_xor(sum, 32, 64);
+    const float m2 = mx > mo ? mx : mo;
+    const float s2 = (mx > -INFINITY ? sum * __expf(mx - m2) : 0.0f) + (mo > -INFINITY ? so * __expf(mo - m2) : 0.0f);
+    if (fh == 0) *partial_slot = float2{m2, s2};
+}
+
 // LDS tile: [rows][8 chunks] of uint4, chunk c of row r stored at c ^ ((r >> 1) & 7): the LDS has 64
 // four-byte banks, so 16 lanes (16 consecutive rows, one logical chunk) must land on 16 distinct 16-byte
 // positions of a 256-byte window, i.e. on distinct (row parity, slot) pairs.
@@ -156,6 +191,22 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__rest
     }
 
     // epilogue: lane holds, for each (tn, tm), row m = .. + lane%32 and n = .. + 8 g + 4 (lane/32) + 0..3
+    if constexpr (EPI == 4) {
+        const int n_partial = 2 * (int)gridDim.x;
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm) {
+            const int mr = m0 + wm * 64 + tm * 32 + fr;
+            const size_t row = (size_t)sign * m_half + (mr < m_half ? mr : m_half - 1);
+            const f32x16 a[2] = {acc[0][tm], acc[1][tm]};
+            float dummy_logit;
+            float2 dummy_pair;
+            const bool live = mr < m_half;
+            ce_partial_row<2>(a, n0 + wn * 64, fh, n, live ? ((const int32_t *)b_p)[row] : -1,
+                              live ? (float *)b_m + row : &dummy_logit,
+                              live ? (float2 *)y + row * n_partial + (blockIdx.x * 2 + wn) : &dummy_pair);
+        }
+        return;
+    }
 #pragma unroll
     for (int tm = 0; tm < 2; ++tm) {
         const int mr = m0 + wm * 64 + tm * 32 + fr;
@@ -175,7 +226,6 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__rest
         }
     }
 }
-
 
 // ------------------------------------------------------------------ 256 x 256 x 32 tiling
 namespace big {
@@ -321,6 +371,22 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // drain the tail loads before LDS is released
 
+    if constexpr (EPI == 4) {
+        const int n_partial = 2 * tiles_n;
+#pragma unroll
+        for (int tm = 0; tm < 4; ++tm) {
+            const int mr = m0 + wm * 128 + tm * 32 + fr;
+            const size_t row = (size_t)sign * m_half + (mr < m_half ? mr : m_half - 1);
+            const f32x16 a[4] = {acc[0][tm], acc[1][tm], acc[2][tm], acc[3][tm]};
+            float dummy_logit;
+            float2 dummy_pair;
+            const bool live = mr < m_half;
+            ce_partial_row<4>(a, n0 + wn * 128, fh, n, live ? ((const int32_t *)b_p)[row] : -1,
+                              live ? (float *)b_m + row : &dummy_logit,
+                              live ? (float2 *)y + row * n_partial + (tcol * 2 + wn) : &dummy_pair);
+        }
+        return;
+    }
 #pragma unroll
     for (int tm = 0; tm < 4; ++tm) {
         const int mr = m0 + wm * 128 + tm * 32 + fr;
@@ -355,6 +421,7 @@ void launch_t(const void *x, const void *wt_p, const void *wt_m, const void *b_p
     case 0: ZO_L(0); break;
     case 1: ZO_L(1); break;
     case 2: ZO_L(2); break;
+    case 4: ZO_L(4); break;
     default: ZO_L(3); break;
     }
 #undef ZO_L
@@ -384,6 +451,7 @@ hipError_t launch_big_t(const void *x, const void *wt_p, const void *wt_m, const
     case 0: ZO_B(0) break;
     case 1: ZO_B(1) break;
     case 2: ZO_B(2) break;
+    case 4: ZO_B(4) break;
     default: ZO_B(3) break;
     }
 #undef ZO_B
@@ -399,6 +467,11 @@ bool use_big(int n_sign, int m_half, int n, int k)
 }
 
 }  // namespace
+
+int mfma_ce_partials(int n_sign, int m_half, int n, int k)
+{
+    return use_big(n_sign, m_half, n, k) ? 2 * ((n + big::BN - 1) / big::BN) : 2 * ((n + BN - 1) / BN);
+}
 
 bool mfma_linear_supported(int m_half, int n, int k) { return m_half >= 1 && n >= 8 && n % 8 == 0 && k >= BK && k % BK == 0; }
 

@@ -69,6 +69,12 @@ bool mfma_linear_supported(int m_half, int n, int k);
 hipError_t launch_linear_mfma(const void *x, const void *wt_p, const void *wt_m, const void *b_p, const void *b_m,
                               void *y, int dtype, int n_sign, int m_half, int n, int k, int epilogue,
                               hipStream_t s);
+// Epilogue 4 of launch_linear_mfma (LM head fused with the cross-entropy reduction): instead of logits it
+// leaves mfma_ce_partials(...) (max, sum-exp) pairs per row in `y` (float2[rows][pairs]) and the target
+// logit of each row in `b_m` (float[rows]); `b_p` carries the int32 targets.  launch_ce_finish merges them.
+int mfma_ce_partials(int n_sign, int m_half, int n, int k);
+hipError_t launch_ce_finish(const void *partials, int n_partial, const float *target_logit, const int32_t *target,
+                            double *row_loss, int rows, hipStream_t s);
 bool mfma_attention_supported(int seq, int d_head);
 hipError_t launch_attention_mfma(const void *qkv, void *out, int dtype, int n_seq, int seq, int n_heads,
                                  int d_head, hipStream_t s);
