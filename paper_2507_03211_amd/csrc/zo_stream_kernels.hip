@@ -4,6 +4,8 @@
 // All of them are one pass over the parameters with z regenerated in registers from its
 // counter: 16-byte coalesced loads and stores, four independent Philox blocks per thread for
 // instruction-level parallelism, no LDS except for the transposing stage.
+#include <type_traits>
+
 #include "zo_kernels.h"
 #include "zo_rng.hip.h"
 #include "zo_types.hip.h"
@@ -174,16 +176,19 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
     }
 
     // transposing tile: rows r0.., cols c0..  (cols % 4 == 0 is guaranteed by the caller)
+    // A thread owns a 4 x 4 patch (4 adjacent rows, one Philox block each), so each of its 4 columns goes
+    // into the transposed LDS tile as one packed store of 4 adjacent rows (no 2-byte scatter).
     constexpr int T = (int)kStageTile;
-    constexpr int LD = T + 16 / (int)sizeof(W);     // padded row, keeps 16-byte alignment
+    constexpr int LD = T + 4;                       // row stride: keeps 8-byte (16-byte for fp32) alignment, spreads banks
     __shared__ __attribute__((aligned(16))) W sp[T * LD];
     __shared__ __attribute__((aligned(16))) W sm[SINGLE ? 1 : T * LD];
     const uint32_t r0 = (tile / d.tiles_c) * T, c0 = (tile % d.tiles_c) * T;
-    // read: thread -> (row = tid/16 + 16*it, four columns 4*(tid%16)..+3): one Philox block each
+    const uint32_t rb = threadIdx.x / 16, cb = threadIdx.x % 16;
+    const uint32_t c = c0 + 4 * cb;
+    W vp[4][4], vm[4][4];                           // [row in patch][column in patch]
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-        const uint32_t lr = threadIdx.x / 16 + 16 * it, lc = 4 * (threadIdx.x % 16);
-        const uint32_t r = r0 + lr, c = c0 + lc;
+        const uint32_t r = r0 + 4 * rb + it;
         if (r < d.rows && c < d.cols) {
             const uint64_t i0 = (uint64_t)r * d.cols + c;
             W raw[4];
@@ -191,17 +196,33 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
             else *(uint4 *)raw = *(const uint4 *)(src + i0);
             if constexpr (SINGLE) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) sp[(lc + e) * LD + lr] = raw[e];
+                for (int e = 0; e < 4; ++e) vp[it][e] = raw[e];
             } else {
                 float z[4];
                 normal4(philox_block(seed, d.tid, i0 / 4), z);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float th = Prec<DT>::w2f(raw[e]);
-                    sp[(lc + e) * LD + lr] = Prec<DT>::f2w(__builtin_fmaf(eps, z[e], th));
-                    sm[(lc + e) * LD + lr] = Prec<DT>::f2w(__builtin_fmaf(-eps, z[e], th));
+                    vp[it][e] = Prec<DT>::f2w(__builtin_fmaf(eps, z[e], th));
+                    vm[it][e] = Prec<DT>::f2w(__builtin_fmaf(-eps, z[e], th));
                 }
             }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { vp[it][e] = W(0); vm[it][e] = W(0); }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        W colp[4] = {vp[0][e], vp[1][e], vp[2][e], vp[3][e]};
+        W colm[4] = {vm[0][e], vm[1][e], vm[2][e], vm[3][e]};
+        W *dstp = sp + (4 * cb + e) * LD + 4 * rb, *dstm = sm + (4 * cb + e) * LD + 4 * rb;
+        if constexpr (sizeof(W) == 2) {
+            *(uint2 *)dstp = *(const uint2 *)colp;
+            if constexpr (!SINGLE) *(uint2 *)dstm = *(const uint2 *)colm;
+        } else {
+            *(uint4 *)dstp = *(const uint4 *)colp;
+            if constexpr (!SINGLE) *(uint4 *)dstm = *(const uint4 *)colm;
         }
     }
     __syncthreads();
@@ -211,11 +232,19 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
         const uint64_t o0 = (uint64_t)(c0 + oc) * d.rows + r0 + seg;
         const bool full = (r0 + seg + 16 <= d.rows) && ((d.rows * sizeof(W)) % 16 == 0);
         if (full) {
-            constexpr int NV = 16 * (int)sizeof(W) / 16;
+            constexpr int NV = 16 * (int)sizeof(W) / 16;      // 16-byte pieces per 16 elements
+            using LdsVec = typename std::conditional<sizeof(W) == 2, uint2, uint4>::type;
+            constexpr int PER = 16 / (int)sizeof(LdsVec);     // LDS reads per 16-byte piece
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                ((uint4 *)(dp + o0))[v] = ((const uint4 *)(sp + oc * LD + seg))[v];
-                if constexpr (!SINGLE) ((uint4 *)(dm + o0))[v] = ((const uint4 *)(sm + oc * LD + seg))[v];
+                LdsVec pp[PER], pm[PER];
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    pp[j] = ((const LdsVec *)(sp + oc * LD + seg))[v * PER + j];
+                    if constexpr (!SINGLE) pm[j] = ((const LdsVec *)(sm + oc * LD + seg))[v * PER + j];
+                }
+                ((uint4 *)(dp + o0))[v] = *(const uint4 *)pp;
+                if constexpr (!SINGLE) ((uint4 *)(dm + o0))[v] = *(const uint4 *)pm;
             }
         } else {
             for (uint32_t e = 0; e < 16 && r0 + seg + e < d.rows; ++e) {
