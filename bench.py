@@ -86,40 +86,48 @@ def cpu_baseline(cfgd, name):
         dtm = (time.perf_counter() - t0) / n
         return {"value": full_tokens / dtm, "unit": "tokens/s", "cores": _cores(), "kind": "oracle",
                 "sample": "%d whole steps of the same workload" % n}
-    s_seq = min(cfgd["seq"], 64 if d >= 4096 else 128)
     s_vocab = min(V, 8192)
-    ocfg = zo.Config(1, d, cfgd["n_heads"], f, s_vocab, s_seq, dt)
+    ocfg = zo.Config(1, d, cfgd["n_heads"], f, s_vocab, cfgd["seq"], dt)
     theta = zi.make_weights(ocfg.shapes(), dt, seed=0)
-    tok = zi.make_tokens(1, s_seq, s_vocab)
     blk = ocfg.block_ids(0)
     eps = cfgd["eps"]
     t0 = time.perf_counter()
     wp = [zo.widen(zo.axpy_z(theta[i], dt, 0, i, eps), dt) for i in blk]
     wm = [zo.widen(zo.axpy_z(theta[i], dt, 0, i, -np.float32(eps)), dt) for i in blk]
     t_stage = time.perf_counter() - t0
-    h = zo.embed(tok, zo.widen(theta[0], dt), zo.widen(theta[1], dt))
-    t0 = time.perf_counter()
-    hp = zo.block_forward(h, dict(zip(zo.BLOCK_TENSORS, wp)), ocfg.n_heads, ocfg.ln_eps)
-    hm = zo.block_forward(h, dict(zip(zo.BLOCK_TENSORS, wm)), ocfg.n_heads, ocfg.ln_eps)
-    t_fwd = time.perf_counter() - t0
     t0 = time.perf_counter()
     for i in blk:
         zo.axpy_z(theta[i], dt, 0, i, -1e-7, out=theta[i])
     t_upd = time.perf_counter() - t0
-    t0 = time.perf_counter()
     e64 = zo.widen(theta[0], dt)
-    for hh in (hp, hm):
-        zo.next_token_loss(zo.head_logits(hh, zo.widen(theta[2 + 16], dt), zo.widen(theta[3 + 16], dt), e64, ocfg.ln_eps), tok)
-    t_head = time.perf_counter() - t0
+    # token sample: grown until the whole sample is worth about ten seconds of CPU work (or the full sequence)
+    s_seq, s_batch = min(cfgd["seq"], 64), 1
+    while True:
+        tok = zi.make_tokens(s_batch, s_seq, s_vocab)
+        h = zo.embed(tok, e64, zo.widen(theta[1], dt))
+        t0 = time.perf_counter()
+        hp = zo.block_forward(h, dict(zip(zo.BLOCK_TENSORS, wp)), ocfg.n_heads, ocfg.ln_eps)
+        hm = zo.block_forward(h, dict(zip(zo.BLOCK_TENSORS, wm)), ocfg.n_heads, ocfg.ln_eps)
+        t_fwd = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        for hh in (hp, hm):
+            zo.next_token_loss(zo.head_logits(hh, zo.widen(theta[2 + 16], dt), zo.widen(theta[3 + 16], dt), e64, ocfg.ln_eps), tok)
+        t_head = time.perf_counter() - t0
+        if t_stage + t_upd + t_fwd + t_head >= 10.0 or (s_seq >= cfgd["seq"] and s_batch >= cfgd["batch"]):
+            break
+        if s_seq < cfgd["seq"]:
+            s_seq = min(cfgd["seq"], s_seq * 4)
+        else:
+            s_batch = min(cfgd["batch"], s_batch * 4)
     per_block_params = sum(theta[i].size for i in blk)
     embed_params = V * d + cfgd["max_pos"] * d
     fixed = (t_stage + t_upd) * (L + embed_params / per_block_params)
-    per_token = (L * t_fwd + t_head * (V / s_vocab)) / s_seq
+    per_token = (L * t_fwd + t_head * (V / s_vocab)) / (s_seq * s_batch)
     step_s = fixed + per_token * full_tokens
     return {"value": full_tokens / step_s, "unit": "tokens/s", "cores": _cores(), "kind": "oracle",
-            "sample": "1 of %d blocks at real width with 1 x %d tokens and a %d-row LM head, timed %.1f s; per-parameter cost "
+            "sample": "1 of %d blocks at real width with %d x %d tokens and a %d-row LM head, timed %.1f s; per-parameter cost "
                       "(z, W+-, update) scaled to all parameters, per-token cost to %d tokens (extrapolated)"
-                      % (L, s_seq, s_vocab, t_stage + t_fwd + t_upd + t_head, full_tokens)}
+                      % (L, s_batch, s_seq, s_vocab, t_stage + t_fwd + t_upd + t_head, full_tokens)}
 
 
 def main():
