@@ -42,7 +42,7 @@ typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers across the loop
 
 template <int DT, int DH>
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const uint16_t *__restrict__ qkv, uint16_t *__restrict__ out, int seq,
+__global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(const uint16_t *__restrict__ qkv, uint16_t *__restrict__ out, int seq,
                                                         int n_heads)
 {
     constexpr int CH = DH / 8;            // 16-byte chunks per K / V row
