@@ -14,8 +14,8 @@
 // Two tilings:
 //  * 256 x 256 x 64, 4 waves of 128 x 128 (4 x 4 MFMA tiles, 256 accumulator registers), one
 //    workgroup per CU.  Operand tiles go from global memory straight into LDS
-//    (global_load_lds_dwordx4, no register staging), whole 128-byte lines per tile row, into two
-//    64 KiB stages: one slab is in flight while one is multiplied.  16-byte chunks are XOR-swizzled
+//    (global_load_lds_dwordx4, no register staging), whole 128-byte lines per tile row; the 160 KiB
+//    of LDS hold three stages of the activation tile and two of the weight tile.  16-byte chunks are XOR-swizzled
 //    on the global side so that fragment reads are free of bank conflicts.  Workgroups are renumbered so that
 //    each XCD (its own L2) owns a contiguous band of 8 tile-rows and walks it column by column.
 //  * 128 x 128 x 64, 4 waves of 64 x 64, register-staged double buffer: for shapes with too few
@@ -230,10 +230,10 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__rest
 // ------------------------------------------------------------------ 256 x 256 x 32 tiling
 namespace big {
 
-constexpr int BM = 256, BN = 256, BK = 64, ST = 2;
-constexpr int kTileU4 = BM * (BK / 8);          // uint4 per operand tile (2048)
-constexpr int kStageU4 = 2 * kTileU4;           // x tile then w tile
-constexpr int kLdsBytes = ST * kStageU4 * 16;   // 128 KiB
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int STX = 3, STW = 2;                 // LDS stages of the activation tile / of the weight tile
+constexpr int kTileU4 = BM * (BK / 8);          // uint4 per operand tile (2048 = 32 KiB)
+constexpr int kLdsBytes = (STX + STW) * kTileU4 * 16;   // 160 KiB: all of a CU's LDS
 constexpr int kGroupM = 8;                      // tile-rows per band
 
 // 16 bytes per lane from global memory straight into LDS: lane L lands at lds_off + 16 L.
@@ -286,14 +286,21 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     }
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
     const int nk = k / BK;
-    auto issue = [&](int t) {
-        const int k0 = (t < nk ? t : nk - 1) * BK;                   // past the end: reload the last slab (never multiplied)
-        const uint32_t st = lds_base + (uint32_t)(t % ST) * (kStageU4 * 16) + (uint32_t)wave * 8192u;
+    // x slab t lives in x stage t % 3, w slab t in w stage t % 2 (after the three x stages)
+    auto x_stage = [&](int t) { return lds_base + (uint32_t)(t % STX) * (kTileU4 * 16) + (uint32_t)wave * 8192u; };
+    auto w_stage = [&](int t) { return lds_base + (uint32_t)(STX + t % STW) * (kTileU4 * 16) + (uint32_t)wave * 8192u; };
+    auto k_of = [&](int t) { return (t < nk ? t : nk - 1) * BK; };      // past the end: reload the last slab (never multiplied)
+    auto issue_x = [&](int t) {
+        const int k0 = k_of(t);
+        const uint32_t st = x_stage(t);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            gload_lds16(xg[i] + k0, st + i * 1024u);
-            gload_lds16(wg[i] + k0, st + kTileU4 * 16 + i * 1024u);
-        }
+        for (int i = 0; i < 8; ++i) gload_lds16(xg[i] + k0, st + i * 1024u);
+    };
+    auto issue_w = [&](int t) {
+        const int k0 = k_of(t);
+        const uint32_t st = w_stage(t);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) gload_lds16(wg[i] + k0, st + i * 1024u);
     };
 
     f32x16 acc[4][4];
@@ -308,8 +315,8 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     const int xrow = (wm * 128 + fr) * 8, wrow = (wn * 128 + fr) * 8;     // uint4 index of the lane's first rows
     uint4 wfa[4], xfa[4], wfb[4], xfb[4];                                 // two fragment sets: one multiplies while one loads
     auto load_frags = [&](int slab, int ks, uint4 (&wf)[4], uint4 (&xf)[4]) {
-        const uint4 *xs = smem + (slab % ST) * kStageU4;
-        const uint4 *ws = xs + kTileU4;
+        const uint4 *xs = smem + (slab % STX) * kTileU4;
+        const uint4 *ws = smem + (STX + slab % STW) * kTileU4;
         const int slot = (2 * ks + fh) ^ sw;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -324,50 +331,57 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
             for (int tm = 0; tm < 4; ++tm) acc[tn][tm] = mfma32<DT>(wf[tn], xf[tm], acc[tn][tm]);
     };
 
-    // Software pipeline over two 64 KiB stages.  The barrier sits before the last quarter of a slab's
-    // multiplies, once this wave's last LDS reads of slab kt are in registers: the stage is refilled with
-    // slab kt+2 at once, which then has the rest of this slab and three quarters of the next to land.
+    // Software pipeline.  The 160 KiB of LDS hold three stages of the activation tile and two of the weight
+    // tile, so half of every slab's loads are issued two slab-times ahead and only the other half one ahead:
+    // with a single slab of lookahead for everything the multiplies wait on memory latency.  The barrier sits
+    // before the last quarter of a slab's multiplies, once this wave's last LDS reads of slab kt are in
+    // registers.  Loads are spread over the whole slab, one between several multiplies, so that they never
+    // queue up at the texture-address unit while the matrix pipe runs dry.
     // sched_barrier(0) pins the order (the compiler would sink each LDS read down to its first use).
-    issue(0);
-    issue(1);
-    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    issue_x(0);
+    issue_w(0);
+    issue_x(1);
+    issue_w(1);
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");               // slab 0 landed
     __builtin_amdgcn_s_barrier();
     load_frags(0, 0, wfa, xfa);
+    // multiplies j0 .. j1-1 of a 4 x 4 fragment product, with a load slipped in before multiply j whenever
+    // (j - j0) % every == 0, up to `nload` of them, taken from `ptrs[first ..]` into LDS at `st`
+    auto mma_ld = [&](const uint4 (&wf)[4], const uint4 (&xf)[4], int j0, int j1, const uint16_t *const (&ptrs)[8], int kofs,
+                      uint32_t st, int first, int nload, int every) {
+#pragma unroll
+        for (int j = j0; j < j1; ++j) {
+            const int q = (j - j0) / every;
+            if ((j - j0) % every == 0 && q < nload) {
+                gload_lds16(ptrs[first + q] + kofs, st + (first + q) * 1024u);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            acc[j >> 2][j & 3] = mfma32<DT>(wf[j >> 2], xf[j & 3], acc[j >> 2][j & 3]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     for (int kt = 0; kt < nk; ++kt) {
+        // x(kt+2) goes into the activation stage that slab kt-1 left at the previous barrier: its 8 loads sit
+        // under the multiplies before this slab's barrier; w(kt+2) can only follow the barrier: its 8 loads sit
+        // under the 28 multiplies after it.
+        const int kx = k_of(kt + 2), kw = kx;
+        const uint32_t stx = x_stage(kt + 2), stw = w_stage(kt + 2);
         load_frags(kt, 1, wfb, xfb);
         __builtin_amdgcn_sched_barrier(0);
-        mma16(wfa, xfa);
-        __builtin_amdgcn_sched_barrier(0);
+        mma_ld(wfa, xfa, 0, 16, xg, kx, stx, 0, 3, 5);
         load_frags(kt, 2, wfa, xfa);
         __builtin_amdgcn_sched_barrier(0);
-        mma16(wfb, xfb);
-        __builtin_amdgcn_sched_barrier(0);
+        mma_ld(wfb, xfb, 0, 16, xg, kx, stx, 3, 3, 5);
         load_frags(kt, 3, wfb, xfb);
         __builtin_amdgcn_sched_barrier(0);
-        mma16(wfa, xfa);
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");    // slab kt+1 landed; slab kt fully in registers
+        mma_ld(wfa, xfa, 0, 4, xg, kx, stx, 6, 2, 2);
+        // slab kt+1 landed (only x(kt+2), the 8 newest loads, may still be out); slab kt fully in registers
+        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
+        mma_ld(wfa, xfa, 4, 16, wg, kw, stw, 0, 4, 3);
         load_frags(kt + 1, 0, wfa, xfa);                                // past the end: a reloaded slab, never multiplied
         __builtin_amdgcn_sched_barrier(0);
-        // refill the stage of slab kt, one load between two multiplies: a burst of 16 would hold the wave at
-        // the texture-address queue while the matrix pipe runs dry
-        {
-            const int t = kt + 2;
-            const int k0 = (t < nk ? t : nk - 1) * BK;
-            const uint32_t st = lds_base + (uint32_t)(t % ST) * (kStageU4 * 16) + (uint32_t)wave * 8192u;
-#pragma unroll
-            for (int tn = 0; tn < 4; ++tn)
-#pragma unroll
-                for (int tm = 0; tm < 4; ++tm) {
-                    const int i = (tn * 4 + tm) >> 1;
-                    if (((tn * 4 + tm) & 1) == 0) gload_lds16(xg[i] + k0, st + i * 1024u);
-                    else gload_lds16(wg[i] + k0, st + kTileU4 * 16 + i * 1024u);
-                    __builtin_amdgcn_sched_barrier(0);
-                    acc[tn][tm] = mfma32<DT>(wfb[tn], xfb[tm], acc[tn][tm]);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-        }
+        mma_ld(wfb, xfb, 0, 16, wg, kw, stw, 4, 4, 4);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // drain the tail loads before LDS is released
 
