@@ -401,23 +401,80 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
         }
         return;
     }
+    // Output through LDS so that global stores are whole rows: in the MFMA layout a lane holds runs of 4
+    // consecutive columns of ONE row and a wave instruction would touch 32 rows with 16 or 32 bytes each.
+    // Every wave stages 32 rows x 128 columns at a time in a region of its own (no workgroup barrier inside),
+    // XOR-swizzled so that both the run-wise writes and the row-wise 16-byte reads are free of bank conflicts.
+    __syncthreads();                                                 // every wave is done with the operand stages
+    constexpr bool kOut16 = (EPI == 0 || EPI == 1);                  // 2-byte outputs; else fp32
+    char *stage = (char *)smem + wave * 16384;
+    const int ncol0 = n0 + wn * 128;
+    float bvals[4][4][4];                                            // bias of the lane's 16 runs (same for every tm)
+#pragma unroll
+    for (int tn = 0; tn < 4; ++tn)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int nc = ncol0 + tn * 32 + 8 * g + 4 * fh;
+            uint2 braw = uint2{0u, 0u};
+            if (EPI != 3 && nc < n) braw = *(const uint2 *)(bias + nc);
+            bvals[tn][g][0] = Prec<DT>::w2f((uint16_t)(braw.x & 0xffff));
+            bvals[tn][g][1] = Prec<DT>::w2f((uint16_t)(braw.x >> 16));
+            bvals[tn][g][2] = Prec<DT>::w2f((uint16_t)(braw.y & 0xffff));
+            bvals[tn][g][3] = Prec<DT>::w2f((uint16_t)(braw.y >> 16));
+        }
 #pragma unroll
     for (int tm = 0; tm < 4; ++tm) {
-        const int mr = m0 + wm * 128 + tm * 32 + fr;
-        if (mr >= m_half) continue;
-        const size_t row = (size_t)sign * m_half + mr;
 #pragma unroll
-        for (int tn = 0; tn < 4; ++tn) {
+        for (int tn = 0; tn < 4; ++tn)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int nc = n0 + wn * 128 + tn * 32 + 8 * g + 4 * fh;
-                if (nc >= n) continue;
                 float v[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[tn][tm][4 * g + e];
-                epilogue_store<DT, EPI>(v, bias, y, row, n, nc);
+                for (int e = 0; e < 4; ++e) {
+                    v[e] = acc[tn][tm][4 * g + e];
+                    if constexpr (EPI != 3) v[e] += bvals[tn][g][e];
+                    if constexpr (EPI == 1) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+                }
+                const int run = tn * 8 + 2 * g + fh;                 // which run of 4 columns (0..31) of the row
+                if constexpr (kOut16) {
+                    uint2 o;
+                    o.x = (uint32_t)Prec<DT>::acc2a(v[0]) | ((uint32_t)Prec<DT>::acc2a(v[1]) << 16);
+                    o.y = (uint32_t)Prec<DT>::acc2a(v[2]) | ((uint32_t)Prec<DT>::acc2a(v[3]) << 16);
+                    *(uint2 *)(stage + fr * 256 + ((run ^ fr) << 3)) = o;          // 8-byte slots, XOR by the row
+                } else {
+                    *(float4 *)(stage + fr * 512 + ((run ^ (fr & 15)) << 4)) = float4{v[0], v[1], v[2], v[3]};
+                }
+            }
+        const int mbase = m0 + wm * 128 + tm * 32;
+        asm volatile("" ::: "memory");          // the wave's LDS operations execute in order; keep the compiler to it too
+        if constexpr (kOut16) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int r = 4 * i + (lane >> 4), c16 = lane & 15;               // 16 lanes x 16 bytes = one 256-byte row
+                uint4 q = *(const uint4 *)(stage + r * 256 + ((c16 ^ (r >> 1)) << 4));
+                if (r & 1) q = uint4{q.z, q.w, q.x, q.y};                        // odd rows hold the two runs swapped
+                const int mr = mbase + r, nc = ncol0 + c16 * 8;
+                if (mr < m_half && nc < n) *(uint4 *)((uint16_t *)y + ((size_t)sign * m_half + mr) * n + nc) = q;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int r = 2 * i + (lane >> 5), c = lane & 31;                 // 32 lanes x 16 bytes = one 512-byte row
+                const float4 q = *(const float4 *)(stage + r * 512 + ((c ^ (r & 15)) << 4));
+                const int mr = mbase + r, nc = ncol0 + c * 4;
+                if (mr < m_half && nc < n) {
+                    float4 *p = (float4 *)((float *)y + ((size_t)sign * m_half + mr) * n + nc);
+                    if constexpr (EPI == 2) {
+                        float4 h = *p;
+                        h.x += q.x; h.y += q.y; h.z += q.z; h.w += q.w;
+                        *p = h;
+                    } else {
+                        *p = q;
+                    }
+                }
             }
         }
+        asm volatile("" ::: "memory");
     }
 }
 
