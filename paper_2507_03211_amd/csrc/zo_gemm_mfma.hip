@@ -331,12 +331,25 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
             for (int tm = 0; tm < 4; ++tm) acc[tn][tm] = mfma32<DT>(wf[tn], xf[tm], acc[tn][tm]);
     };
 
+    // One fragment of set (wf, xf) for k-step ks of a slab, in the order the multiplies need them:
+    // wf0, xf0, xf1, xf2, xf3, wf1, wf2, wf3.
+    auto frag1 = [&](int slab, int ks, int idx, uint4 (&wf)[4], uint4 (&xf)[4]) {
+        const uint4 *xs = smem + (slab % STX) * kTileU4;
+        const uint4 *ws = smem + (STX + slab % STW) * kTileU4;
+        const int slot = (2 * ks + fh) ^ sw;
+        if (idx == 0) wf[0] = ws[wrow + slot];
+        else if (idx <= 4) xf[idx - 1] = xs[xrow + (idx - 1) * 256 + slot];
+        else wf[idx - 4] = ws[wrow + (idx - 4) * 256 + slot];
+    };
+
     // Software pipeline.  The 160 KiB of LDS hold three stages of the activation tile and two of the weight
     // tile, so half of every slab's loads are issued two slab-times ahead and only the other half one ahead:
-    // with a single slab of lookahead for everything the multiplies wait on memory latency.  The barrier sits
-    // before the last quarter of a slab's multiplies, once this wave's last LDS reads of slab kt are in
-    // registers.  Loads are spread over the whole slab, one between several multiplies, so that they never
-    // queue up at the texture-address unit while the matrix pipe runs dry.
+    // with a single slab of lookahead for everything the multiplies wait on memory latency.  One wave per SIMD
+    // means nothing else hides an instruction that is slow to issue, so neither the global->LDS loads nor the
+    // LDS fragment reads come in bursts: each sits alone between two multiplies and issues while the matrix
+    // pipe works on the one before.  The fragments of a quarter slab (16 multiplies) are read during the quarter
+    // before it, into the set of registers the quarter before that used.  The barrier sits in the middle of
+    // the third quarter, once this wave's last LDS reads of slab kt are in registers.
     // sched_barrier(0) pins the order (the compiler would sink each LDS read down to its first use).
     issue_x(0);
     issue_w(0);
@@ -345,15 +358,21 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     asm volatile("s_waitcnt vmcnt(16)" ::: "memory");               // slab 0 landed
     __builtin_amdgcn_s_barrier();
     load_frags(0, 0, wfa, xfa);
-    // multiplies j0 .. j1-1 of a 4 x 4 fragment product, with a load slipped in before multiply j whenever
-    // (j - j0) % every == 0, up to `nload` of them, taken from `ptrs[first ..]` into LDS at `st`
-    auto mma_ld = [&](const uint4 (&wf)[4], const uint4 (&xf)[4], int j0, int j1, const uint16_t *const (&ptrs)[8], int kofs,
-                      uint32_t st, int first, int nload, int every) {
+    // Multiplies j0 .. j1-1 of the 4 x 4 fragment product of set (wf, xf).  Before multiply j:
+    //  * fragment (j - rj0) / revery of set (nwf, nxf) is read for k-step nks of slab nslab, when that divides;
+    //  * load lfirst + (j - lj0) / levery of `ptrs` goes out into LDS at `st`, when that divides, `nload` in all.
+    auto mma_rl = [&](const uint4 (&wf)[4], const uint4 (&xf)[4], int j0, int j1, uint4 (&nwf)[4], uint4 (&nxf)[4], int nslab,
+                      int nks, int rj0, int revery, const uint16_t *const (&ptrs)[8], int kofs, uint32_t st, int lfirst,
+                      int nload, int lj0, int levery) {
 #pragma unroll
         for (int j = j0; j < j1; ++j) {
-            const int q = (j - j0) / every;
-            if ((j - j0) % every == 0 && q < nload) {
-                gload_lds16(ptrs[first + q] + kofs, st + (first + q) * 1024u);
+            if (j >= rj0 && (j - rj0) % revery == 0 && (j - rj0) / revery < 8) {
+                frag1(nslab, nks, (j - rj0) / revery, nwf, nxf);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (j >= lj0 && (j - lj0) % levery == 0 && (j - lj0) / levery < nload) {
+                const int q = lfirst + (j - lj0) / levery;
+                gload_lds16(ptrs[q] + kofs, st + q * 1024u);
                 __builtin_amdgcn_sched_barrier(0);
             }
             acc[j >> 2][j & 3] = mfma32<DT>(wf[j >> 2], xf[j & 3], acc[j >> 2][j & 3]);
@@ -362,26 +381,19 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     };
     for (int kt = 0; kt < nk; ++kt) {
         // x(kt+2) goes into the activation stage that slab kt-1 left at the previous barrier: its 8 loads sit
-        // under the multiplies before this slab's barrier; w(kt+2) can only follow the barrier: its 8 loads sit
-        // under the 28 multiplies after it.
+        // under the 40 multiplies before this slab's barrier; w(kt+2) can only follow the barrier: its 8 loads
+        // sit under the 24 multiplies after it.
         const int kx = k_of(kt + 2), kw = kx;
         const uint32_t stx = x_stage(kt + 2), stw = w_stage(kt + 2);
-        load_frags(kt, 1, wfb, xfb);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_ld(wfa, xfa, 0, 16, xg, kx, stx, 0, 3, 5);
-        load_frags(kt, 2, wfa, xfa);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_ld(wfb, xfb, 0, 16, xg, kx, stx, 3, 3, 5);
-        load_frags(kt, 3, wfb, xfb);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_ld(wfa, xfa, 0, 4, xg, kx, stx, 6, 2, 2);
+        mma_rl(wfa, xfa, 0, 16, wfb, xfb, kt, 1, 1, 2, xg, kx, stx, 0, 3, 0, 6);
+        mma_rl(wfb, xfb, 0, 16, wfa, xfa, kt, 2, 1, 2, xg, kx, stx, 3, 3, 0, 6);
+        mma_rl(wfa, xfa, 0, 8, wfb, xfb, kt, 3, 0, 1, xg, kx, stx, 6, 2, 2, 4);
         // slab kt+1 landed (only x(kt+2), the 8 newest loads, may still be out); slab kt fully in registers
         asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        mma_ld(wfa, xfa, 4, 16, wg, kw, stw, 0, 4, 3);
-        load_frags(kt + 1, 0, wfa, xfa);                                // past the end: a reloaded slab, never multiplied
-        __builtin_amdgcn_sched_barrier(0);
-        mma_ld(wfb, xfb, 0, 16, wg, kw, stw, 4, 4, 4);
+        mma_rl(wfa, xfa, 8, 16, wfb, xfb, kt, 3, 99, 1, wg, kw, stw, 0, 3, 8, 3);
+        // past the end: fragments of a reloaded slab, never multiplied
+        mma_rl(wfb, xfb, 0, 16, wfa, xfa, kt + 1, 0, 1, 2, wg, kw, stw, 3, 5, 0, 3);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // drain the tail loads before LDS is released
 
