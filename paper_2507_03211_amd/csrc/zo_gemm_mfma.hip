@@ -421,21 +421,51 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     constexpr bool kOut16 = (EPI == 0 || EPI == 1);                  // 2-byte outputs; else fp32
     char *stage = (char *)smem + wave * 16384;
     const int ncol0 = n0 + wn * 128;
-    float bvals[4][4][4];                                            // bias of the lane's 16 runs (same for every tm)
+    // Bias: 2-byte outputs take it before the rounding, so per run of the MFMA layout (the same 16 runs for
+    // every tm); fp32 outputs take it after the LDS pass, where a lane always holds the same 4 columns.
+    float bvals[kOut16 ? 4 : 1][4][4];
 #pragma unroll
-    for (int tn = 0; tn < 4; ++tn)
+    for (int tn = 0; tn < (kOut16 ? 4 : 0); ++tn)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int nc = ncol0 + tn * 32 + 8 * g + 4 * fh;
             uint2 braw = uint2{0u, 0u};
-            if (EPI != 3 && nc < n) braw = *(const uint2 *)(bias + nc);
+            if (nc < n) braw = *(const uint2 *)(bias + nc);
             bvals[tn][g][0] = Prec<DT>::w2f((uint16_t)(braw.x & 0xffff));
             bvals[tn][g][1] = Prec<DT>::w2f((uint16_t)(braw.x >> 16));
             bvals[tn][g][2] = Prec<DT>::w2f((uint16_t)(braw.y & 0xffff));
             bvals[tn][g][3] = Prec<DT>::w2f((uint16_t)(braw.y >> 16));
         }
+    // Residual epilogue: the 16 reads of the running sum that a pass needs are all issued one pass ahead, so a
+    // tile pays the memory latency once and not once per row group (a load may not overtake an earlier store
+    // that the compiler cannot tell apart from it).
+    float4 hres[2][16];
+    auto load_res = [&](int tm, float4 (&h)[16]) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int r = 2 * i + (lane >> 5), c = lane & 31;
+            const int mr = m0 + wm * 128 + tm * 32 + r, nc = ncol0 + c * 4;
+            h[i] = float4{0.f, 0.f, 0.f, 0.f};
+            if (mr < m_half && nc < n) h[i] = *(const float4 *)((const float *)y + ((size_t)sign * m_half + mr) * n + nc);
+        }
+    };
+    float bias4[4] = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (EPI == 2) {
+        load_res(0, hres[0]);
+        const int nc = ncol0 + (lane & 31) * 4;
+        if (nc < n) {
+            const uint2 braw = *(const uint2 *)(bias + nc);
+            bias4[0] = Prec<DT>::w2f((uint16_t)(braw.x & 0xffff));
+            bias4[1] = Prec<DT>::w2f((uint16_t)(braw.x >> 16));
+            bias4[2] = Prec<DT>::w2f((uint16_t)(braw.y & 0xffff));
+            bias4[3] = Prec<DT>::w2f((uint16_t)(braw.y >> 16));
+        }
+    }
 #pragma unroll
     for (int tm = 0; tm < 4; ++tm) {
+        if constexpr (EPI == 2) {
+            if (tm < 3) load_res(tm + 1, hres[(tm + 1) & 1]);
+        }
 #pragma unroll
         for (int tn = 0; tn < 4; ++tn)
 #pragma unroll
@@ -444,7 +474,7 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     v[e] = acc[tn][tm][4 * g + e];
-                    if constexpr (EPI != 3) v[e] += bvals[tn][g][e];
+                    if constexpr (kOut16) v[e] += bvals[tn][g][e];
                     if constexpr (EPI == 1) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
                 }
                 const int run = tn * 8 + 2 * g + fh;                 // which run of 4 columns (0..31) of the row
@@ -477,8 +507,8 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
                 if (mr < m_half && nc < n) {
                     float4 *p = (float4 *)((float *)y + ((size_t)sign * m_half + mr) * n + nc);
                     if constexpr (EPI == 2) {
-                        float4 h = *p;
-                        h.x += q.x; h.y += q.y; h.z += q.z; h.w += q.w;
+                        float4 h = hres[tm & 1][i];
+                        h.x += q.x + bias4[0]; h.y += q.y + bias4[1]; h.z += q.z + bias4[2]; h.w += q.w + bias4[3];
                         *p = h;
                     } else {
                         *p = q;
