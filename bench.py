@@ -24,8 +24,10 @@ PEAK_HBM_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=8)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 20; 3 for the streamed configuration)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default 3; 1 streamed)")
+    ap.add_argument("--batch", type=int, default=None, help="override the configuration's batch size")
+    ap.add_argument("--seq", type=int, default=None, help="override the configuration's sequence length (longer-context variants)")
     ap.add_argument("--config", default="opt-13b", help="tiny | opt-125m | opt-1.3b | opt-13b | opt-175b (streamed)")
     ap.add_argument("--host-blocks", type=int, default=6,
                     help="streamed configs: number of distinct real-shape pinned host blocks; the layers cycle through them "
@@ -143,10 +145,20 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
-    c = zi.CONFIGS[args.config]
+    c = dict(zi.CONFIGS[args.config])
+    dname = {0: "f64", 1: "bf16", 2: "f16"}[c["dtype"]]
+    if args.batch:
+        c["batch"] = args.batch
+    if args.seq:
+        c["seq"] = args.seq
+        c["max_pos"] = max(c["max_pos"], args.seq)
     dev = "cuda:0"
     shapes = zi.tensor_shapes(c["n_layers"], c["d_model"], c["d_ffn"], c["vocab"], c["max_pos"])
     streamed = args.config == "opt-175b"
+    if args.steps is None:
+        args.steps = 3 if streamed else 20
+    if args.warmup is None:
+        args.warmup = 1 if streamed else 3
     host_ring = None
     if not streamed:
         tensors = device_weights(torch, shapes, c["dtype"], dev)
@@ -210,15 +222,16 @@ def main():
     zo_amd.zo_free(h)
 
     tokens_per_step = c["batch"] * c["seq"]
-    dname = {0: "f64", 1: "bf16", 2: "f16"}[c["dtype"]]
     kernels = {}
     for name, (ms, n, work) in prof.items():
         if n == 0:
             continue
         rate = work / (ms * 1e-3) if ms > 0 else 0.0
         is_flop = name in ("linear", "attention")
+        ach_k = rate / (1e12 if is_flop else 1e9)
+        peak_k = PEAK_TFLOPS[dname] if is_flop else PEAK_HBM_GBS
         kernels[name] = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
-                         "achieved": rate / (1e12 if is_flop else 1e9), "unit": "TFLOP/s" if is_flop else "GB/s"}
+                         "achieved": ach_k, "unit": "TFLOP/s" if is_flop else "GB/s", "frac_of_peak": ach_k / peak_k}
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     dom_ms, dom_n, dom_work = prof[dom]
     if dom in ("linear", "attention"):
