@@ -68,6 +68,8 @@ def _clib():
                                     ctypes.c_uint64, ctypes.c_void_p]
         lib.zo_oracle_axpy_z.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64,
                                          ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_float]
+        lib.zo_oracle_axpy_z_sr.argtypes = lib.zo_oracle_axpy_z.argtypes
+        lib.zo_oracle_sr_array.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64]
         lib.zo_oracle_f32_to_bf16.argtypes = [ctypes.c_float]
         lib.zo_oracle_f32_to_bf16.restype = ctypes.c_uint16
         lib.zo_oracle_f32_to_f16.argtypes = [ctypes.c_float]
@@ -115,18 +117,33 @@ def storage_dtype(dtype):
     return {FP32: np.float32, BF16: np.uint16, FP16: np.float16}[dtype]
 
 
-def axpy_z(src, dtype, seed, tensor_id, scale, first=0, out=None):
+def axpy_z(src, dtype, seed, tensor_id, scale, first=0, out=None, stochastic=False):
     """rn(fma(scale, z, src)) element-wise, in the storage type.  `src` is the
     slice of the tensor that starts at element `first`.  Returns a new array
-    unless `out` is given (out may be src: in place)."""
+    unless `out` is given (out may be src: in place).  `stochastic=True`
+    replaces the round-to-nearest by the opt-in stochastic rounding (2-byte
+    types only; random words from Philox tag 3)."""
     src = np.ascontiguousarray(src)
     assert src.dtype == storage_dtype(dtype), (src.dtype, dtype)
     if out is None:
         out = np.empty_like(src)
     assert out.flags.c_contiguous and out.dtype == src.dtype and out.shape == src.shape
-    _clib().zo_oracle_axpy_z(src.ctypes.data, out.ctypes.data, int(dtype), int(seed), int(tensor_id),
-                             int(first), int(src.size), ctypes.c_float(float(np.float32(scale))))
+    assert not (stochastic and dtype == FP32), "stochastic rounding is for the 2-byte storage types"
+    fn = _clib().zo_oracle_axpy_z_sr if stochastic else _clib().zo_oracle_axpy_z
+    fn(src.ctypes.data, out.ctypes.data, int(dtype), int(seed), int(tensor_id),
+       int(first), int(src.size), ctypes.c_float(float(np.float32(scale))))
     return out
+
+
+def sr_round(values, words, dtype):
+    """Stochastic rounding of fp32 `values` with the given uint32 random words,
+    element-wise, into the 2-byte storage type (bf16 as uint16 patterns)."""
+    v = np.ascontiguousarray(values, dtype=np.float32)
+    w = np.ascontiguousarray(words, dtype=np.uint32)
+    assert v.shape == w.shape and dtype in (BF16, FP16)
+    out = np.empty(v.shape, dtype=np.uint16)
+    _clib().zo_oracle_sr_array(v.ctypes.data, w.ctypes.data, out.ctypes.data, int(dtype), int(v.size))
+    return out if dtype == BF16 else out.view(np.float16)
 
 
 def to_storage(x, dtype):
@@ -274,10 +291,10 @@ def step_scalar(lr, g):
     return np.float32(-(float(np.float32(lr)) * g))
 
 
-def perturb_all(cfg, theta, seed, scale, ids=None):
+def perturb_all(cfg, theta, seed, scale, ids=None, stochastic=False):
     """Alg. 1 PerturbParameters over the tensors `ids` (all by default), in place."""
     for t in (range(cfg.n_tensors) if ids is None else ids):
-        axpy_z(theta[t], cfg.dtype, seed, t, scale, out=theta[t])
+        axpy_z(theta[t], cfg.dtype, seed, t, scale, out=theta[t], stochastic=stochastic)
 
 
 def zo_step_literal(cfg, theta, tokens, seed, eps, lr):
@@ -304,11 +321,12 @@ def dual_loss_fused(cfg, theta, tokens, seed, eps):
     return loss_of_storage(cfg, plus, tokens), loss_of_storage(cfg, minus, tokens)
 
 
-def zo_step_fused(cfg, theta, tokens, seed, eps, lr):
-    """Same step with theta untouched by the perturbation: W+- = rn(theta +- eps z)."""
+def zo_step_fused(cfg, theta, tokens, seed, eps, lr, stochastic_update=False):
+    """Same step with theta untouched by the perturbation: W+- = rn(theta +- eps z).
+    `stochastic_update` rounds the update of Eq. 2 (and only it) stochastically."""
     l_plus, l_minus = dual_loss_fused(cfg, theta, tokens, seed, eps)
     g = projected_gradient(l_plus, l_minus, eps)
-    perturb_all(cfg, theta, seed, step_scalar(lr, g))
+    perturb_all(cfg, theta, seed, step_scalar(lr, g), stochastic=stochastic_update)
     return l_plus, l_minus, g
 
 

@@ -253,3 +253,94 @@ void zo_oracle_axpy_z(const void *src, void *dst, int dtype, uint64_t seed, uint
         }
     }
 }
+
+/* ------------------------------------------- stochastic rounding (opt-in) */
+
+/* An opt-in variant of the update of Eq. 2, not part of the paper's method:
+ * the paper stores parameters in 16 bits ("FP16 mode", Sec. 7) and applies
+ * theta <- theta - eta g z in that type; with round-to-nearest almost every
+ * such update of a weight is lost (|eta g z| << ulp(theta) / 2, tested in
+ * tests/test_oracle_step.py).  Stochastic rounding keeps the update unbiased:
+ * the fp32 value v = fma(s, z, theta) goes to one of its two neighbours in
+ * the storage type, the farther-from-zero one with probability equal to the
+ * fraction of the way v lies from the nearer-to-zero one.
+ *
+ * Exact definition (integer arithmetic only, so the bits reproduce anywhere):
+ * write |v| = (n + f) * u with u the spacing of the storage type at |v|,
+ * n an integer and 0 <= f < 1.  F = floor(f * 2^24).  With r = word >> 8
+ * (the top 24 bits of the element's random word) the magnitude becomes
+ * (n + 1) * u if r < F and n * u otherwise; the sign is kept.  A value the
+ * storage type represents has f = 0 and never moves.  Non-finite v passes
+ * through as under round-to-nearest; a magnitude that rounds up past the
+ * largest finite value becomes infinity.
+ *
+ * The random word of element i is word (i % 4) of the Philox block with
+ * counter (i / 4, tensor id, tag 3) under the step's seed: independent of the
+ * z of the same element (tag 0). */
+uint16_t zo_oracle_sr_bf16(float v, uint32_t word)
+{
+    uint32_t bits;
+    memcpy(&bits, &v, 4);
+    const uint32_t sign = (bits >> 16) & 0x8000u, mag = bits & 0x7FFFFFFFu;
+    if (mag >= 0x7F800000u) return zo_oracle_f32_to_bf16(v);
+    /* bf16 keeps the top 16 bits of the fp32 pattern: n = those, f = the low 16 bits / 2^16 */
+    const uint32_t n = mag >> 16, F = (mag & 0xFFFFu) << 8, r = word >> 8;
+    return (uint16_t)(sign | (n + (r < F ? 1u : 0u)));
+}
+
+uint16_t zo_oracle_sr_f16(float v, uint32_t word)
+{
+    uint32_t bits;
+    memcpy(&bits, &v, 4);
+    const uint32_t sign = (bits >> 16) & 0x8000u, mag = bits & 0x7FFFFFFFu;
+    if (mag >= 0x7F800000u) return zo_oracle_f32_to_f16(v);
+    const uint32_t e = mag >> 23, m = mag & 0x7FFFFFu, r = word >> 8;
+    uint32_t n, F;
+    if (e >= 143u) return (uint16_t)(sign | 0x7C00u);          /* |v| >= 2^16: beyond the half range */
+    if (e >= 113u) {
+        /* normal half: exponent field e - 112, ten fraction bits kept, thirteen dropped */
+        n = ((e - 112u) << 10) | (m >> 13);
+        F = (m & 0x1FFFu) << 11;
+    } else {
+        /* below 2^-14 the spacing is 2^-24: |v| = sig * 2^(ee - 150), so n + f = sig / 2^s with s = 126 - ee */
+        const uint32_t sig = e ? (m | 0x800000u) : m, ee = e ? e : 1u;
+        const uint32_t s = 126u - ee;                           /* 14 .. 125 */
+        if (s <= 24u) {
+            n = sig >> s;
+            F = (sig & ((1u << s) - 1u)) << (24u - s);
+        } else {
+            n = 0u;
+            F = (s - 24u) < 32u ? sig >> (s - 24u) : 0u;
+        }
+    }
+    return (uint16_t)(sign | (n + (r < F ? 1u : 0u)));
+}
+
+/* dst[i] = sr(fma(scale, z[i], src[i])): as zo_oracle_axpy_z with the rounding above.
+ * dtype 1 (bf16) or 2 (fp16) only. */
+void zo_oracle_axpy_z_sr(const void *src, void *dst, int dtype, uint64_t seed, uint32_t tensor_id,
+                         uint64_t first, uint64_t n, float scale)
+{
+    if (n == 0) return;
+    #pragma omp parallel for schedule(static)
+    for (int64_t jj = (int64_t)(first / 4); jj <= (int64_t)((first + n - 1) / 4); ++jj) {
+        uint32_t w[4], rw[4];
+        float z[4];
+        block_for(seed, tensor_id, 0u, (uint64_t)jj, w);
+        block_for(seed, tensor_id, 3u, (uint64_t)jj, rw);
+        zo_oracle_normal_pair(w[0], w[1], &z[0], &z[1]);
+        zo_oracle_normal_pair(w[2], w[3], &z[2], &z[3]);
+        for (int l = 0; l < 4; ++l) {
+            uint64_t i = 4u * (uint64_t)jj + (uint64_t)l;
+            if (i < first || i >= first + n) continue;
+            const float v = fmaf(scale, z[l], load_as_f32(src, dtype, i - first));
+            ((uint16_t *)dst)[i - first] = dtype == 1 ? zo_oracle_sr_bf16(v, rw[l]) : zo_oracle_sr_f16(v, rw[l]);
+        }
+    }
+}
+
+/* Element-wise stochastic rounding of n fp32 values with given random words (for the pins). */
+void zo_oracle_sr_array(const float *v, const uint32_t *word, uint16_t *out, int dtype, uint64_t n)
+{
+    for (uint64_t i = 0; i < n; ++i) out[i] = dtype == 1 ? zo_oracle_sr_bf16(v[i], word[i]) : zo_oracle_sr_f16(v[i], word[i]);
+}
