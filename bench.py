@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--host-blocks", type=int, default=6,
                     help="streamed configs: number of distinct real-shape pinned host blocks; the layers cycle through them "
                          "(the full 175B model needs 348 GB of pinned memory, more than a box may pin)")
+    ap.add_argument("--stochastic-update", action="store_true",
+                    help="round the update of Eq. 2 stochastically into the 16-bit storage type (opt-in variant)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy, a kernel of known HBM traffic that calibrates "
@@ -194,6 +196,8 @@ def main():
     copy_stream = torch.cuda.Stream(device=dev) if streamed else None
     torch.cuda.synchronize()
     h = zo_amd.zo_init_model(cfg, tensors, ws, nbytes, c["batch"], c["seq"], stream, copy_stream)
+    if args.stochastic_update:
+        zo_amd.zo_set_update_rounding(h, zo_amd.ZO_ROUND_STOCHASTIC)
 
     def step(i):
         zo_amd.zo_step(h, tokens, c["batch"], c["seq"], i, c["eps"], c["lr"], zo_amd.ZO_MODE_FUSED, want_host=False)
@@ -262,7 +266,8 @@ def main():
         "dtype": dname, "data": "synthetic",
         "config": {"workload": args.config, "n_layers": c["n_layers"], "d_model": c["d_model"], "n_heads": c["n_heads"],
                    "d_ffn": c["d_ffn"], "vocab": c["vocab"], "batch": c["batch"], "seq_len": c["seq"], "eps": c["eps"],
-                   "lr": c["lr"], "mode": "fused", "residency": "pinned-host blocks, streamed" if streamed else "hbm"},
+                   "lr": c["lr"], "mode": "fused", "update_rounding": "stochastic" if args.stochastic_update else "nearest",
+                   "residency": "pinned-host blocks, streamed" if streamed else "hbm"},
         "roofline": roof,
         "kernels": kernels,
         "last_step": {"l_plus": lp, "l_minus": lm, "g": g, "device_flags": flags},

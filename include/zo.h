@@ -149,6 +149,18 @@ int zo_stream_end(zo_model *m, float lr, double *host_g, double *host_loss_pm);
  * Alg. 2 never applies the last one).  No-op when nothing is pending. */
 int zo_flush_pending(zo_model *m);
 
+/* How the update of Eq. 2 is rounded into a 16-bit storage type.  ZO_ROUND_NEAREST (the default, and the
+ * only rounding of every perturbation) is round-to-nearest-even.  ZO_ROUND_STOCHASTIC is an opt-in
+ * variant that is not in the paper: at its learning rates a nearest-rounded update of a 16-bit weight
+ * is almost always lost, the stochastic one is unbiased.  With |v| = (n + f) u, u the type's spacing at
+ * |v| = |fma(s, z, theta)|, the magnitude becomes (n + 1) u when the top 24 bits of the element's random
+ * word are below floor(f 2^24) and n u otherwise; the word of element i is word i % 4 of the Philox block
+ * with counter (i / 4, tensor id, tag 3) under the step's seed.  Applies to every later update of this
+ * model, deferred ones included.  ZO_EINVAL for a ZO_FP32 model or an unknown mode. */
+#define ZO_ROUND_NEAREST 0
+#define ZO_ROUND_STOCHASTIC 1
+int zo_set_update_rounding(zo_model *m, int mode);
+
 /* Device-side status word accumulated by the kernels: bit 0 = non-finite loss / skipped
  * update, bit 1 = token id out of range.  Synchronises the compute stream. */
 int zo_device_flags(zo_model *m, uint32_t *host_flags);
@@ -186,6 +198,10 @@ int zo_kernel_normal_pairs(const uint32_t *words, float *z, uint64_t n_pairs, vo
  * read from device memory instead (as the update inside zo_step does). */
 int zo_kernel_axpy_z(const void *src, void *dst, int dtype, uint64_t n, uint64_t seed,
                      uint32_t tensor_id, float scale, const float *dev_scale, void *stream);
+
+/* The same with the stochastic rounding of zo_set_update_rounding (ZO_BF16 / ZO_FP16 only). */
+int zo_kernel_axpy_z_sr(const void *src, void *dst, int dtype, uint64_t n, uint64_t seed,
+                        uint32_t tensor_id, float scale, const float *dev_scale, void *stream);
 
 /* W+ = rn(theta + eps z), W- = rn(theta - eps z) for a [rows, cols] row-major tensor, written
  * transposed ([cols, rows], the layout the GEMMs read) when `transpose` is non-zero. */

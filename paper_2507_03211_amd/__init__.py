@@ -15,14 +15,15 @@ ZO_FP32, ZO_BF16, ZO_FP16 = 0, 1, 2
 ZO_RESIDENT, ZO_STREAMED = 0, 1
 ZO_MODE_LITERAL, ZO_MODE_FUSED = 0, 1
 ZO_PHASE_PREFETCH, ZO_PHASE_COMPUTE, ZO_PHASE_WRITEBACK = 1, 2, 4
+ZO_ROUND_NEAREST, ZO_ROUND_STOCHASTIC = 0, 1
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "libzo.so")
 
 EXPORTS = (
     "zo_workspace_bytes", "zo_init_model", "zo_perturb", "zo_dual_forward", "zo_step", "zo_stream_block",
-    "zo_stream_begin", "zo_stream_end", "zo_flush_pending", "zo_device_flags", "zo_free", "zo_last_error",
-    "zo_profile_begin", "zo_profile_end",
-    "zo_kernel_z", "zo_kernel_normal_pairs", "zo_kernel_axpy_z", "zo_kernel_stage_pm", "zo_kernel_linear_pm",
+    "zo_stream_begin", "zo_stream_end", "zo_flush_pending", "zo_set_update_rounding", "zo_device_flags", "zo_free",
+    "zo_last_error", "zo_profile_begin", "zo_profile_end",
+    "zo_kernel_z", "zo_kernel_normal_pairs", "zo_kernel_axpy_z", "zo_kernel_axpy_z_sr", "zo_kernel_stage_pm", "zo_kernel_linear_pm",
     "zo_kernel_layernorm_pm", "zo_kernel_attention", "zo_kernel_lmhead_scratch_bytes", "zo_kernel_lmhead_ce",
 )
 
@@ -64,6 +65,7 @@ def lib():
         L.zo_stream_begin.argtypes = [vp, vp, i32, i32, u64, f32]
         L.zo_stream_end.argtypes = [vp, f32, vp, vp]
         L.zo_flush_pending.argtypes = [vp]
+        L.zo_set_update_rounding.argtypes = [vp, i32]
         L.zo_device_flags.argtypes = [vp, ctypes.POINTER(u32)]
         L.zo_free.argtypes = [vp]
         L.zo_profile_begin.argtypes = [vp, i32]
@@ -71,6 +73,7 @@ def lib():
         L.zo_kernel_z.argtypes = [vp, u64, u64, u32, u64, vp]
         L.zo_kernel_normal_pairs.argtypes = [vp, vp, u64, vp]
         L.zo_kernel_axpy_z.argtypes = [vp, vp, i32, u64, u64, u32, f32, vp, vp]
+        L.zo_kernel_axpy_z_sr.argtypes = [vp, vp, i32, u64, u64, u32, f32, vp, vp]
         L.zo_kernel_stage_pm.argtypes = [vp, vp, vp, i32, i32, i32, i32, u64, u32, f32, vp]
         L.zo_kernel_linear_pm.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.zo_kernel_layernorm_pm.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]
@@ -167,6 +170,10 @@ def zo_flush_pending(model):
     _check(lib().zo_flush_pending(model))
 
 
+def zo_set_update_rounding(model, mode):
+    _check(lib().zo_set_update_rounding(model, mode))
+
+
 def zo_device_flags(model):
     v = ctypes.c_uint32()
     _check(lib().zo_device_flags(model, ctypes.byref(v)))
@@ -202,6 +209,10 @@ def zo_kernel_normal_pairs(words, z, n_pairs, stream=None):
 
 def zo_kernel_axpy_z(src, dst, dtype, n, seed, tensor_id, scale, dev_scale=None, stream=None):
     _check(lib().zo_kernel_axpy_z(_ptr(src), _ptr(dst), dtype, n, seed, tensor_id, scale, _ptr(dev_scale), _stream(stream)))
+
+
+def zo_kernel_axpy_z_sr(src, dst, dtype, n, seed, tensor_id, scale, dev_scale=None, stream=None):
+    _check(lib().zo_kernel_axpy_z_sr(_ptr(src), _ptr(dst), dtype, n, seed, tensor_id, scale, _ptr(dev_scale), _stream(stream)))
 
 
 def zo_kernel_stage_pm(theta, w_plus, w_minus, dtype, rows, cols, transpose, seed, tensor_id, eps, stream=None):

@@ -167,6 +167,7 @@ struct zo_model {
     bool slot_dirty[2];
     bool pending;
     uint64_t pending_seed;
+    int update_rounding;               // ZO_ROUND_*: how the update of Eq. 2 goes into a 16-bit type
     bool step_open;
     int next_block;
     uint64_t step_seed;
@@ -229,8 +230,9 @@ int check_batch(const zo_model *m, const int32_t *tokens, int batch, int seq)
     return ZO_OK;
 }
 
-// in-place theta <- rn(fma(scale, z, theta)) over tensors [first, first + n)
-int axpy_range(zo_model *m, int first, int n, uint64_t seed, float scale, const float *dev_scale)
+// in-place theta <- rn(fma(scale, z, theta)) over tensors [first, first + n); `update` marks the update of
+// Eq. 2, which alone follows the model's rounding mode (a perturbation is always rounded to nearest)
+int axpy_range(zo_model *m, int first, int n, uint64_t seed, float scale, const float *dev_scale, bool update = false)
 {
     if (n <= 0) return ZO_OK;
     const uint64_t c0 = m->descs[first].first_chunk;
@@ -238,7 +240,7 @@ int axpy_range(zo_model *m, int first, int n, uint64_t seed, float scale, const 
     double bytes = 0;
     for (int t = first; t < first + n; ++t) bytes += 2.0 * (double)m->descs[t].numel * elem_bytes(m->cfg.dtype);
     ZO_PROF(m, K_UPDATE, bytes, launch_axpy_multi(wsp_ptr<TensorDesc>(m, m->wsp.descs) + first, n, c0, c1 - c0, m->cfg.dtype, seed, scale,
-                                                  dev_scale, m->compute));
+                                                  dev_scale, update && m->update_rounding == ZO_ROUND_STOCHASTIC, m->compute));
     return ZO_OK;
 }
 
@@ -457,7 +459,7 @@ int stream_compute(zo_model *m, int block, bool forward)
         return fail(ZO_ESTATE, "block %d was not prefetched", block);
     ZO_HIP(hipStreamWaitEvent(m->compute, m->ev_uploaded[slot], 0));
     if (m->pending) {
-        ZO_TRY(axpy_range(m, 2 + kPerBlock * block, kPerBlock, m->pending_seed, 0.0f, m->s_pending));
+        ZO_TRY(axpy_range(m, 2 + kPerBlock * block, kPerBlock, m->pending_seed, 0.0f, m->s_pending, true));
         m->slot_dirty[slot] = true;
     }
     if (forward) ZO_TRY(stage_block(m, block, m->ws + m->wsp.slot[slot], m->step_seed, m->step_eps, false));
@@ -489,8 +491,8 @@ int stream_begin(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_
     const int lnf = 2 + kPerBlock * c.n_layers;
     m->step_seed = seed; m->step_eps = eps; m->step_batch = batch; m->step_seq = seq;
     if (m->pending) {   // Alg. 2: the resident modules take last step's update at their visit
-        ZO_TRY(axpy_range(m, 0, 2, m->pending_seed, 0.0f, m->s_pending));
-        ZO_TRY(axpy_range(m, lnf, 2, m->pending_seed, 0.0f, m->s_pending));
+        ZO_TRY(axpy_range(m, 0, 2, m->pending_seed, 0.0f, m->s_pending, true));
+        ZO_TRY(axpy_range(m, lnf, 2, m->pending_seed, 0.0f, m->s_pending, true));
     }
     ZO_TRY(stage_globals(m, seq, seed, eps));
     ZO_TRY(embed(m, tokens, 2, batch, seq, m->ws + m->wsp.e_pm[0], m->ws + m->wsp.e_pm[1], m->ws + m->wsp.pos_pm[0],
@@ -660,7 +662,7 @@ extern "C" int zo_step(zo_model *m, const int32_t *tokens, int batch, int seq, u
     if (m->cfg.residency == ZO_RESIDENT) {
         ZO_TRY(zo_dual_forward(m, tokens, batch, seq, seed, eps, mode, nullptr, nullptr));
         ZO_HIP(launch_g_scalar(m->loss_pm, eps, lr, m->g, m->s_cur, m->flags, m->compute));
-        ZO_TRY(axpy_range(m, 0, m->n_tensors, seed, 0.0f, m->s_cur));
+        ZO_TRY(axpy_range(m, 0, m->n_tensors, seed, 0.0f, m->s_cur, true));
         return read_back(m, host_g, host_loss_pm);
     }
     if (mode != ZO_MODE_FUSED) return fail(ZO_EINVAL, "a streamed model supports ZO_MODE_FUSED only");
@@ -711,14 +713,24 @@ extern "C" int zo_stream_end(zo_model *m, float lr, double *host_g, double *host
     return read_back(m, host_g, host_loss_pm);
 }
 
+extern "C" int zo_set_update_rounding(zo_model *m, int mode)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    if (mode != ZO_ROUND_NEAREST && mode != ZO_ROUND_STOCHASTIC) return fail(ZO_EINVAL, "unknown rounding mode %d", mode);
+    if (mode == ZO_ROUND_STOCHASTIC && m->cfg.dtype == ZO_FP32)
+        return fail(ZO_EINVAL, "stochastic rounding is for ZO_BF16 / ZO_FP16 storage");
+    m->update_rounding = mode;
+    return ZO_OK;
+}
+
 extern "C" int zo_flush_pending(zo_model *m)
 {
     if (!m) return fail(ZO_EINVAL, "model is NULL");
     if (m->cfg.residency != ZO_STREAMED || !m->pending) return ZO_OK;
     if (m->step_open) return fail(ZO_ESTATE, "a streamed step is open");
     const int lnf = 2 + kPerBlock * m->cfg.n_layers;
-    ZO_TRY(axpy_range(m, 0, 2, m->pending_seed, 0.0f, m->s_pending));
-    ZO_TRY(axpy_range(m, lnf, 2, m->pending_seed, 0.0f, m->s_pending));
+    ZO_TRY(axpy_range(m, 0, 2, m->pending_seed, 0.0f, m->s_pending, true));
+    ZO_TRY(axpy_range(m, lnf, 2, m->pending_seed, 0.0f, m->s_pending, true));
     ZO_TRY(stream_prefetch(m, 0));
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         if (l + 1 < m->cfg.n_layers) ZO_TRY(stream_prefetch(m, l + 1));
@@ -796,7 +808,19 @@ extern "C" int zo_kernel_axpy_z(const void *src, void *dst, int dtype, uint64_t 
     if (!src || !dst) return fail(ZO_EINVAL, "NULL argument");
     if ((uintptr_t)src % 16 || (uintptr_t)dst % 16) return fail(ZO_EINVAL, "buffers must be 16-byte aligned");
     TensorDesc d{src, dst, n, 0, tensor_id, 0};
-    ZO_HIP(launch_axpy_single(d, dtype, seed, scale, dev_scale, (hipStream_t)stream));
+    ZO_HIP(launch_axpy_single(d, dtype, seed, scale, dev_scale, false, (hipStream_t)stream));
+    return ZO_OK;
+}
+
+extern "C" int zo_kernel_axpy_z_sr(const void *src, void *dst, int dtype, uint64_t n, uint64_t seed, uint32_t tensor_id, float scale,
+                                   const float *dev_scale, void *stream)
+{
+    if (dtype != ZO_BF16 && dtype != ZO_FP16) return fail(ZO_EINVAL, "stochastic rounding is for ZO_BF16 / ZO_FP16 storage (dtype %d)", dtype);
+    if (n == 0) return ZO_OK;
+    if (!src || !dst) return fail(ZO_EINVAL, "NULL argument");
+    if ((uintptr_t)src % 16 || (uintptr_t)dst % 16) return fail(ZO_EINVAL, "buffers must be 16-byte aligned");
+    TensorDesc d{src, dst, n, 0, tensor_id, 0};
+    ZO_HIP(launch_axpy_single(d, dtype, seed, scale, dev_scale, true, (hipStream_t)stream));
     return ZO_OK;
 }
 

@@ -36,9 +36,9 @@ hipError_t launch_z(float *out, uint64_t n, uint64_t seed, uint32_t tid, uint64_
 hipError_t launch_normal_pairs(const uint32_t *words, float *z, uint64_t n_pairs, hipStream_t s);
 // descs in device memory: n_desc consecutive entries whose chunks are chunk_offset .. chunk_offset + total_chunks - 1
 hipError_t launch_axpy_multi(const TensorDesc *dev_descs, int n_desc, uint64_t chunk_offset, uint64_t total_chunks,
-                             int dtype, uint64_t seed, float scale, const float *dev_scale, hipStream_t s);
+                             int dtype, uint64_t seed, float scale, const float *dev_scale, bool stochastic, hipStream_t s);
 hipError_t launch_axpy_single(const TensorDesc &d, int dtype, uint64_t seed, float scale,
-                              const float *dev_scale, hipStream_t s);
+                              const float *dev_scale, bool stochastic, hipStream_t s);
 // both signs (eps) or a plain (transposing) copy when single_copy
 hipError_t launch_stage(const StageBatch &b, int dtype, uint64_t seed, float eps, bool single_copy, hipStream_t s);
 void stage_batch_add(StageBatch &b, const void *src, void *dp, void *dm, uint32_t rows, uint32_t cols,

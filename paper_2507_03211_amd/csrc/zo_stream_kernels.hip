@@ -56,6 +56,19 @@ template <int DT> __device__ __forceinline__ void unpack16(const uint4 &v, float
         }
     }
 }
+// The same with the stochastic rounding; word e serves element e (16-bit types only).
+template <int DT> __device__ __forceinline__ uint4 pack16_sr(const float *f, const uint32_t *word)
+{
+    static_assert(DT != kFP32, "stochastic rounding is for the 16-bit storage types");
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t lo = DT == kBF16 ? sr_to_bf16(f[2 * i], word[2 * i]) : sr_to_f16(f[2 * i], word[2 * i]);
+        const uint32_t hi = DT == kBF16 ? sr_to_bf16(f[2 * i + 1], word[2 * i + 1]) : sr_to_f16(f[2 * i + 1], word[2 * i + 1]);
+        w[i] = lo | (hi << 16);
+    }
+    return uint4{w[0], w[1], w[2], w[3]};
+}
 template <int DT> __device__ __forceinline__ uint4 pack16(const float *f)
 {
     if constexpr (DT == kFP32) {
@@ -69,8 +82,10 @@ template <int DT> __device__ __forceinline__ uint4 pack16(const float *f)
     }
 }
 
-// One workgroup = one chunk of kAxpyChunk elements of one tensor.
-template <int DT>
+// One workgroup = one chunk of kAxpyChunk elements of one tensor.  SR: stochastic instead of nearest
+// rounding into the storage type, with the random word of element i taken from word i % 4 of the
+// Philox block (i / 4, tensor, tag 3) under the same seed.
+template <int DT, bool SR>
 __global__ __launch_bounds__(256) void axpy_z_kernel(const TensorDesc *__restrict__ descs, int n_desc, TensorDesc single,
                                                      uint64_t chunk_offset, uint64_t seed, float scale,
                                                      const float *__restrict__ dev_scale)
@@ -102,15 +117,27 @@ __global__ __launch_bounds__(256) void axpy_z_kernel(const TensorDesc *__restric
         float z[VN];
 #pragma unroll
         for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b);
+        uint32_t rw[SR ? VN : 1];
+        if constexpr (SR) {
+#pragma unroll
+            for (int b = 0; b < VN / 4; ++b) {
+                const u32x4 r = philox_block(seed, d.tid, i0 / 4 + b, 3u);
+                rw[4 * b] = r.x; rw[4 * b + 1] = r.y; rw[4 * b + 2] = r.z; rw[4 * b + 3] = r.w;
+            }
+        }
         if (i0 + VN <= d.numel) {
             float th[VN];
             unpack16<DT>(*(const uint4 *)(src + i0), th);
 #pragma unroll
             for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
-            *(uint4 *)(dst + i0) = pack16<DT>(th);
+            if constexpr (SR) *(uint4 *)(dst + i0) = pack16_sr<DT>(th, rw);
+            else *(uint4 *)(dst + i0) = pack16<DT>(th);
         } else {
-            for (int e = 0; e < VN && i0 + e < d.numel; ++e)
-                dst[i0 + e] = Prec<DT>::f2w(__builtin_fmaf(sc, z[e], Prec<DT>::w2f(src[i0 + e])));
+            for (int e = 0; e < VN && i0 + e < d.numel; ++e) {
+                const float v = __builtin_fmaf(sc, z[e], Prec<DT>::w2f(src[i0 + e]));
+                if constexpr (SR) dst[i0 + e] = DT == kBF16 ? sr_to_bf16(v, rw[e]) : sr_to_f16(v, rw[e]);
+                else dst[i0 + e] = Prec<DT>::f2w(v);
+            }
         }
     }
 }
@@ -273,37 +300,45 @@ hipError_t launch_normal_pairs(const uint32_t *words, float *z, uint64_t n_pairs
 
 template <int DT>
 static hipError_t axpy_launch_t(const TensorDesc *descs, int n_desc, const TensorDesc &single, uint64_t chunk_offset,
-                                uint64_t chunks, uint64_t seed, float scale, const float *dev_scale, hipStream_t s)
+                                uint64_t chunks, uint64_t seed, float scale, const float *dev_scale, bool stochastic,
+                                hipStream_t s)
 {
     if (chunks == 0) return hipSuccess;
     if (chunks > 0x7fffffffull) return hipErrorInvalidValue;
-    axpy_z_kernel<DT><<<dim3((unsigned)chunks), dim3(256), 0, s>>>(descs, n_desc, single, chunk_offset, seed, scale,
-                                                                  dev_scale);
+    const dim3 grid((unsigned)chunks), block(256);
+    if constexpr (DT != kFP32) {
+        if (stochastic) {
+            axpy_z_kernel<DT, true><<<grid, block, 0, s>>>(descs, n_desc, single, chunk_offset, seed, scale, dev_scale);
+            return hipGetLastError();
+        }
+    }
+    if (stochastic) return hipErrorInvalidValue;          // fp32 storage has nothing to round stochastically
+    axpy_z_kernel<DT, false><<<grid, block, 0, s>>>(descs, n_desc, single, chunk_offset, seed, scale, dev_scale);
     return hipGetLastError();
 }
 
 hipError_t launch_axpy_multi(const TensorDesc *dev_descs, int n_desc, uint64_t chunk_offset, uint64_t total_chunks,
-                             int dtype, uint64_t seed, float scale, const float *dev_scale, hipStream_t s)
+                             int dtype, uint64_t seed, float scale, const float *dev_scale, bool stochastic, hipStream_t s)
 {
     TensorDesc none{};
     switch (dtype) {
-    case kFP32: return axpy_launch_t<kFP32>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, s);
-    case kBF16: return axpy_launch_t<kBF16>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, s);
-    case kFP16: return axpy_launch_t<kFP16>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, s);
+    case kFP32: return axpy_launch_t<kFP32>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, stochastic, s);
+    case kBF16: return axpy_launch_t<kBF16>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, stochastic, s);
+    case kFP16: return axpy_launch_t<kFP16>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, stochastic, s);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_axpy_single(const TensorDesc &d, int dtype, uint64_t seed, float scale, const float *dev_scale,
-                              hipStream_t s)
+                              bool stochastic, hipStream_t s)
 {
     const uint64_t chunks = (d.numel + kAxpyChunk - 1) / kAxpyChunk;
     TensorDesc one = d;
     one.first_chunk = 0;
     switch (dtype) {
-    case kFP32: return axpy_launch_t<kFP32>(nullptr, 0, one, 0, chunks, seed, scale, dev_scale, s);
-    case kBF16: return axpy_launch_t<kBF16>(nullptr, 0, one, 0, chunks, seed, scale, dev_scale, s);
-    case kFP16: return axpy_launch_t<kFP16>(nullptr, 0, one, 0, chunks, seed, scale, dev_scale, s);
+    case kFP32: return axpy_launch_t<kFP32>(nullptr, 0, one, 0, chunks, seed, scale, dev_scale, stochastic, s);
+    case kBF16: return axpy_launch_t<kBF16>(nullptr, 0, one, 0, chunks, seed, scale, dev_scale, stochastic, s);
+    case kFP16: return axpy_launch_t<kFP16>(nullptr, 0, one, 0, chunks, seed, scale, dev_scale, stochastic, s);
     }
     return hipErrorInvalidValue;
 }

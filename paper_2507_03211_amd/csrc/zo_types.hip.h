@@ -40,6 +40,36 @@ __device__ __forceinline__ uint16_t f32_to_f16_bits_unfused(float f)
     return f32_to_f16_bits(f);
 }
 
+// Stochastic rounding of an fp32 value into a 16-bit storage type (the opt-in rounding of the update of
+// Eq. 2: round-to-nearest loses almost every update of a 16-bit weight at the paper's learning rates).
+// |v| = (n + f) u with u the type's spacing at |v|: the magnitude becomes (n + 1) u when the word's top
+// 24 bits are below floor(f 2^24), else n u; the sign is kept, representable values never move,
+// non-finite values go the round-to-nearest way.
+__device__ __forceinline__ uint16_t sr_to_bf16(float v, uint32_t word)
+{
+    const uint32_t bits = __float_as_uint(v), mag = bits & 0x7fffffffu;
+    if (mag >= 0x7f800000u) return f32_to_bf16_bits(v);
+    const uint32_t up = (word >> 8) < ((mag & 0xffffu) << 8) ? 1u : 0u;      // the dropped 16 bits are f
+    return (uint16_t)(((bits >> 16) & 0x8000u) | ((mag >> 16) + up));
+}
+__device__ __forceinline__ uint16_t sr_to_f16(float v, uint32_t word)
+{
+    const uint32_t bits = __float_as_uint(v), mag = bits & 0x7fffffffu, sign = (bits >> 16) & 0x8000u;
+    if (mag >= 0x7f800000u) return f32_to_f16_bits(v);
+    const uint32_t e = mag >> 23;
+    if (e >= 143u) return (uint16_t)(sign | 0x7c00u);                       // 2^16 and beyond
+    // 24-bit significand and how many of its low bits lie below the half's last place: 13 for a normal
+    // half, more below 2^-14 where the spacing stays 2^-24
+    const uint32_t sig = (mag & 0x7fffffu) | (e ? 0x800000u : 0u);
+    const uint32_t drop = e >= 113u ? 13u : (e ? 126u - e : 125u);
+    const uint32_t expo = e >= 113u ? (e - 113u) << 10 : 0u;                // sig >> 13 carries the implicit one on top
+    const uint32_t n = expo + (drop < 32u ? sig >> drop : 0u);
+    uint32_t f24;
+    if (drop <= 24u) f24 = (sig & ((1u << drop) - 1u)) << (24u - drop);
+    else f24 = drop - 24u < 32u ? sig >> (drop - 24u) : 0u;
+    return (uint16_t)(sign | (n + ((word >> 8) < f24 ? 1u : 0u)));
+}
+
 // Per-precision types.  W: parameter storage, A: activations between kernels, R: residual
 // stream, Acc: accumulator / statistics.  fp32 parameters run with fp64 activations: g is a
 // difference of two nearly equal losses, and fp32 activation rounding alone would eat the

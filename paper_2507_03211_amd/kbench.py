@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--rows", type=int, default=5120)
     ap.add_argument("--cols", type=int, default=5120)
     ap.add_argument("--transpose", type=int, default=1)
+    ap.add_argument("--stochastic", action="store_true", help="axpy: the stochastically rounded update (16-bit types)")
     a = ap.parse_args()
     code, tdt = DT[a.dtype]
     dev = "cuda:0"
@@ -73,7 +74,9 @@ def main():
         out.update(shape=[a.n_seq, a.seq, a.heads, a.d_head], ms=ms, tflops=flops / ms / 1e9, frac_of_peak=flops / ms / 1e9 / 2500.0)
     elif a.kernel == "axpy":
         t = (0.02 * torch.randn(a.n, device=dev)).to(tdt)
-        ms = timed(lambda: zo.zo_kernel_axpy_z(t, t, code, a.n, 1, 2, 1e-3), a.reps)
+        fn = zo.zo_kernel_axpy_z_sr if a.stochastic else zo.zo_kernel_axpy_z
+        ms = timed(lambda: fn(t, t, code, a.n, 1, 2, 1e-3), a.reps)
+        out["rounding"] = "stochastic" if a.stochastic else "nearest"
         gb = 2.0 * a.n * esz / 1e9
         out.update(n=a.n, ms=ms, gbs=gb / (ms * 1e-3), frac_of_hbm=gb / (ms * 1e-3) / 8000.0, gelem_per_s=a.n / ms / 1e6)
     elif a.kernel == "stage":

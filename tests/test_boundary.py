@@ -52,5 +52,9 @@ def test_host_side_argument_checks():
     with pytest.raises(zo_amd.ZoError):
         zo_amd.zo_kernel_axpy_z(4096, 4096, 9, 16, 1, 0, 1e-3)
     with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_kernel_axpy_z_sr(4096, 4096, zo_amd.ZO_FP32, 16, 1, 0, 1e-3)   # nothing to round stochastically in fp32
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_set_update_rounding(None, zo_amd.ZO_ROUND_STOCHASTIC)
+    with pytest.raises(zo_amd.ZoError):
         zo_amd.zo_kernel_stage_pm(4096, 4096, 4096, 0, 8, 6, 1, 1, 0, 1e-3)     # transposed, cols % 4 != 0
     assert zo_amd.zo_free(None) is None
