@@ -33,9 +33,16 @@ template <int DT> __device__ __forceinline__ f32x16 mfma32(const uint4 &a, const
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
+// Two probabilities into one register, round-to-nearest-even: one packed conversion instead of two
+// single ones and a merge.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 template <int DT> __device__ __forceinline__ uint32_t pack2(float a, float b)
 {
-    return (uint32_t)Prec<DT>::acc2a(a) | ((uint32_t)Prec<DT>::acc2a(b) << 16);
+    const f32x2 v = {a, b};
+    if constexpr (DT == kBF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
@@ -99,11 +106,22 @@ __global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(cons
     const int tj = lane & 15;
     const int tr_key = tj >> 2;                                  // + key base
     const int tr_chan = 16 * ((lane >> 4) & 1) + 4 * (tj & 3);   // + 32 * channel tile
-    auto vt_frag = [&](int kb, int ctile) {
-        const int key = kb + tr_key, chan = ctile * 32 + tr_chan;
-        const uint16_t *p = (const uint16_t *)vs + (size_t)(key * CH + ((chan >> 3) ^ vswz(key))) * 8 + (chan & 7);
+    // Everything of an LDS address that depends on the lane is worked out once, here: the key bases of the
+    // loop are multiples of 4 (V) and 16 or 32 (K), which the swizzles do not see, so inside the loop an
+    // address is one of these plus a compile-time constant.
+    int voff[DH / 32];                                           // element offset of (key tr_key + 4 fh, channel tile c)
+#pragma unroll
+    for (int c = 0; c < DH / 32; ++c) {
+        const int key = 4 * fh + tr_key, chan = c * 32 + tr_chan;
+        voff[c] = (key * CH + ((chan >> 3) ^ vswz(key))) * 8 + (chan & 7);
+    }
+    auto vt_frag = [&](int kb16, int ctile) {                    // keys kb16 + 4 fh + tr_key, kb16 a multiple of 8
+        const uint16_t *p = (const uint16_t *)vs + voff[ctile] + kb16 * CH * 8;
         return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16 *)p);
     };
+    int koff[DH / 16];                                           // u32x4 index of (key fr, k-step s)
+#pragma unroll
+    for (int s = 0; s < DH / 16; ++s) koff[s] = fr * CH + ((2 * s + fh) ^ kswz(fr));
 
     const int q_hi = qt * BQ + BQ - 1 < seq - 1 ? qt * BQ + BQ - 1 : seq - 1;   // last query row of the workgroup
     const int n_tiles = q_hi / BKV + 1;
@@ -129,8 +147,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(cons
             for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
 #pragma unroll
             for (int s = 0; s < DH / 16; ++s) {
-                const int r = kt * 32 + fr;
-                const u32x4 kf = ks[r * CH + ((2 * s + fh) ^ kswz(r))];
+                const u32x4 kf = ks[kt * 32 * CH + koff[s]];
                 sacc[kt] = mfma32<DT>(__builtin_bit_cast(uint4, kf), qf[s], sacc[kt]);
             }
         }
@@ -148,10 +165,9 @@ __global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(cons
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) tmax = sacc[kt][i] > tmax ? sacc[kt][i] : tmax;
-        const float other = __shfl_xor(tmax, 32, 64);
-        tmax = other > tmax ? other : tmax;
-        const float m_new = tmax > m_run ? tmax : m_run;      // finite: key k0 <= q0 <= qrow is never masked
+            for (int i = 0; i < 16; i += 2) tmax = __builtin_fmaxf(__builtin_fmaxf(sacc[kt][i], sacc[kt][i + 1]), tmax);   // three-input maxima
+        tmax = __builtin_fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float m_new = __builtin_fmaxf(tmax, m_run);     // finite: key k0 <= q0 <= qrow is never masked
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
         const float moff = -m_new * sc;
         float psum = 0.0f;
@@ -183,10 +199,9 @@ __global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(cons
             pf.y = pack2<DT>(sacc[kt][rb + 2], sacc[kt][rb + 3]);
             pf.z = pack2<DT>(sacc[kt][rb + 4], sacc[kt][rb + 5]);
             pf.w = pack2<DT>(sacc[kt][rb + 6], sacc[kt][rb + 7]);
-            const int key_a = 16 * s + 4 * fh;
 #pragma unroll
             for (int c = 0; c < DH / 32; ++c) {
-                const v4i16 lo = vt_frag(key_a, c), hi = vt_frag(key_a + 8, c);
+                const v4i16 lo = vt_frag(16 * s, c), hi = vt_frag(16 * s + 8, c);
                 const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
                 oacc[c] = mfma32<DT>(uint4{lo2.x, lo2.y, hi2.x, hi2.y}, pf, oacc[c]);
             }

@@ -239,9 +239,16 @@ constexpr int kGroupM = 8;                      // tile-rows per band
 // 16 bytes per lane from global memory straight into LDS: lane L lands at lds_off + 16 L.
 // Issued from asm so that the waits are ours: the compiler would otherwise drain every
 // outstanding load before the next LDS read, which defeats the overlap.
-__device__ __forceinline__ void gload_lds16(const void *gptr, uint32_t lds_off)
+// The address is a wave-uniform 64-bit base (scalar registers: the k advance of the pipeline costs no vector
+// instruction) plus a 32-bit per-lane byte offset that stays the same for the whole tile.
+__device__ __forceinline__ void gload_lds16(uint64_t base, uint32_t lane_off, uint32_t lds_off)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_off) : "memory");
+}
+__device__ __forceinline__ uint64_t uniform64(uint64_t v)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
 }
 
 template <int DT, int EPI>
@@ -274,15 +281,17 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     // chunk slot ^ (row / 2 mod 8): 16 consecutive rows of one logical chunk then sit on 16 distinct
     // 16-byte positions of the 64-bank (256-byte wide) LDS, so fragment reads are conflict-free.
     const int lrow = lane >> 3, lslot = lane & 7;
-    const uint16_t *xg[8], *wg[8];
+    const uint64_t xbase = uniform64((uint64_t)(uintptr_t)(xa + (size_t)m0 * k));
+    const uint64_t wbase = uniform64((uint64_t)(uintptr_t)(wt + (size_t)n0 * k));
+    uint32_t xg[8], wg[8];                                           // byte offsets from the tile's first row
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int row = (wave * 8 + i) * 8 + lrow;
         const int chunk = lslot ^ ((row >> 1) & 7);
         int xr = m0 + row; xr = xr < m_half ? xr : m_half - 1;       // clamp: masked at the store
         int wr = n0 + row; wr = wr < n ? wr : n - 1;
-        xg[i] = xa + (size_t)xr * k + chunk * 8;
-        wg[i] = wt + (size_t)wr * k + chunk * 8;
+        xg[i] = ((uint32_t)(xr - m0) * (uint32_t)k + chunk * 8) * 2u;
+        wg[i] = ((uint32_t)(wr - n0) * (uint32_t)k + chunk * 8) * 2u;
     }
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
     const int nk = k / BK;
@@ -291,16 +300,16 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     auto w_stage = [&](int t) { return lds_base + (uint32_t)(STX + t % STW) * (kTileU4 * 16) + (uint32_t)wave * 8192u; };
     auto k_of = [&](int t) { return (t < nk ? t : nk - 1) * BK; };      // past the end: reload the last slab (never multiplied)
     auto issue_x = [&](int t) {
-        const int k0 = k_of(t);
+        const uint64_t b = xbase + 2u * (uint32_t)k_of(t);
         const uint32_t st = x_stage(t);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) gload_lds16(xg[i] + k0, st + i * 1024u);
+        for (int i = 0; i < 8; ++i) gload_lds16(b, xg[i], st + i * 1024u);
     };
     auto issue_w = [&](int t) {
-        const int k0 = k_of(t);
+        const uint64_t b = wbase + 2u * (uint32_t)k_of(t);
         const uint32_t st = w_stage(t);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) gload_lds16(wg[i] + k0, st + i * 1024u);
+        for (int i = 0; i < 8; ++i) gload_lds16(b, wg[i], st + i * 1024u);
     };
 
     f32x16 acc[4][4];
@@ -359,20 +368,22 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     __builtin_amdgcn_s_barrier();
     load_frags(0, 0, wfa, xfa);
     // Multiplies j0 .. j1-1 of the 4 x 4 fragment product of set (wf, xf).  Before multiply j:
-    //  * fragment (j - rj0) / revery of set (nwf, nxf) is read for k-step nks of slab nslab, when that divides;
-    //  * load lfirst + (j - lj0) / levery of `ptrs` goes out into LDS at `st`, when that divides, `nload` in all.
+    //  * fragments rper (j - rj0) / revery .. + rper - 1 of set (nwf, nxf) are read for k-step nks of slab nslab,
+    //    when that divides;
+    //  * load lfirst + (j - lj0) / levery (lane offsets `offs` from the scalar base `gbase`) goes out into LDS at `st`, when that divides, `nload` in all.
     auto mma_rl = [&](const uint4 (&wf)[4], const uint4 (&xf)[4], int j0, int j1, uint4 (&nwf)[4], uint4 (&nxf)[4], int nslab,
-                      int nks, int rj0, int revery, const uint16_t *const (&ptrs)[8], int kofs, uint32_t st, int lfirst,
-                      int nload, int lj0, int levery) {
+                      int nks, int rj0, int revery, int rper, const uint32_t (&offs)[8], uint64_t gbase, uint32_t st,
+                      int lfirst, int nload, int lj0, int levery) {
 #pragma unroll
         for (int j = j0; j < j1; ++j) {
-            if (j >= rj0 && (j - rj0) % revery == 0 && (j - rj0) / revery < 8) {
-                frag1(nslab, nks, (j - rj0) / revery, nwf, nxf);
+            if (j >= rj0 && (j - rj0) % revery == 0 && (j - rj0) / revery * rper < 8) {
+#pragma unroll
+                for (int r = 0; r < rper; ++r) frag1(nslab, nks, (j - rj0) / revery * rper + r, nwf, nxf);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (j >= lj0 && (j - lj0) % levery == 0 && (j - lj0) / levery < nload) {
                 const int q = lfirst + (j - lj0) / levery;
-                gload_lds16(ptrs[q] + kofs, st + q * 1024u);
+                gload_lds16(gbase, offs[q], st + q * 1024u);
                 __builtin_amdgcn_sched_barrier(0);
             }
             acc[j >> 2][j & 3] = mfma32<DT>(wf[j >> 2], xf[j & 3], acc[j >> 2][j & 3]);
@@ -383,17 +394,19 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
         // x(kt+2) goes into the activation stage that slab kt-1 left at the previous barrier: its 8 loads sit
         // under the 40 multiplies before this slab's barrier; w(kt+2) can only follow the barrier: its 8 loads
         // sit under the 24 multiplies after it.
-        const int kx = k_of(kt + 2), kw = kx;
+        const uint64_t kx = xbase + 2u * (uint32_t)k_of(kt + 2), kw = wbase + 2u * (uint32_t)k_of(kt + 2);
         const uint32_t stx = x_stage(kt + 2), stw = w_stage(kt + 2);
-        mma_rl(wfa, xfa, 0, 16, wfb, xfb, kt, 1, 1, 2, xg, kx, stx, 0, 3, 0, 6);
-        mma_rl(wfb, xfb, 0, 16, wfa, xfa, kt, 2, 1, 2, xg, kx, stx, 3, 3, 0, 6);
-        mma_rl(wfa, xfa, 0, 8, wfb, xfb, kt, 3, 0, 1, xg, kx, stx, 6, 2, 2, 4);
+        mma_rl(wfa, xfa, 0, 16, wfb, xfb, kt, 1, 1, 2, 1, xg, kx, stx, 0, 3, 0, 6);
+        mma_rl(wfb, xfb, 0, 16, wfa, xfa, kt, 2, 1, 2, 1, xg, kx, stx, 3, 3, 0, 6);
+        // the last fragments of slab kt, two reads at a time, so that they have landed when the barrier's wait comes
+        mma_rl(wfa, xfa, 0, 8, wfb, xfb, kt, 3, 0, 1, 2, xg, kx, stx, 6, 2, 4, 2);
         // slab kt+1 landed (only x(kt+2), the 8 newest loads, may still be out); slab kt fully in registers
         asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        mma_rl(wfa, xfa, 8, 16, wfb, xfb, kt, 3, 99, 1, wg, kw, stw, 0, 3, 8, 3);
-        // past the end: fragments of a reloaded slab, never multiplied
-        mma_rl(wfb, xfb, 0, 16, wfa, xfa, kt + 1, 0, 1, 2, wg, kw, stw, 3, 5, 0, 3);
+        mma_rl(wfa, xfa, 8, 16, wfb, xfb, kt, 3, 99, 1, 1, wg, kw, stw, 0, 3, 8, 3);
+        // the first fragments of slab kt+1 early in the quarter: the loop's back edge waits for all LDS reads.
+        // Past the end these are fragments of a reloaded slab, never multiplied
+        mma_rl(wfb, xfb, 0, 16, wfa, xfa, kt + 1, 0, 0, 1, 1, wg, kw, stw, 3, 5, 0, 3);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // drain the tail loads before LDS is released
 
