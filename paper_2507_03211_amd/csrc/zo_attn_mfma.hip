@@ -49,15 +49,17 @@ typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers across the loop
 
 template <int DT, int DH>
-__global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(const uint16_t *__restrict__ qkv, uint16_t *__restrict__ out, int seq,
+__global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(const uint16_t *__restrict__ qkv, uint16_t *__restrict__ out, int seq,
                                                         int n_heads)
 {
     constexpr int CH = DH / 8;            // 16-byte chunks per K / V row
     // K and V tiles, both [key][channel] as they sit in memory, 16-byte chunks XOR-swizzled per key so that
     // the MFMA fragment reads of K (32 keys, one chunk) and the transposing reads of V (4 keys x 32 bytes
     // per 16 lanes) are free of conflicts on the 64-bank LDS.
-    __shared__ u32x4 ks[BKV * CH];
-    __shared__ u32x4 vs[BKV * CH];
+    // Two buffers each: the tile after the current one arrives (global memory straight into LDS) while the
+    // current one is multiplied.
+    __shared__ u32x4 ks2[2][BKV * CH];
+    __shared__ u32x4 vs2[2][BKV * CH];
     auto kswz = [](int r) { return DH == 128 ? (r & 15) : ((r >> 1) & 7); };
     auto vswz = [](int r) { return DH == 128 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); };
 
@@ -65,7 +67,8 @@ __global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(cons
     const int head = blockIdx.y, sq = blockIdx.z;
     const int d = n_heads * DH, ld = 3 * d;
     const uint16_t *base = qkv + (size_t)sq * seq * ld + head * DH;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, and known to be: it feeds scalar operands
     const int fr = lane & 31, fh = lane >> 5;
     const int q0 = qt * BQ + wave * 32;          // first query row of this wave
     const int qrow = q0 + fr;                    // this lane's query row
@@ -85,20 +88,50 @@ __global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(cons
     float m_run = -INFINITY, l_run = 0.0f;
     const float sc = 1.4426950408889634f / __builtin_sqrtf((float)DH);
 
-    // global -> LDS assignment for a K/V tile: consecutive lanes take consecutive 16-byte chunks of one key row
-    // (whole cache lines per wave instruction); 256 threads cover 256 / CH keys per pass
-    constexpr int RPP = 256 / CH;         // key rows per pass
-    constexpr int NLD = BKV / RPP;
-    const int lch = tid % CH, lrow = tid / CH;
-    u32x4 kreg[NLD], vreg[NLD];
-#define ZO_ATTN_LOAD_TILE(K0)                                                        \
-    _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                                \
-        int kr = (K0) + lrow + RPP * i;                                              \
-        kr = kr < seq ? kr : seq - 1;                                                \
-        const uint16_t *kp = base + (size_t)kr * ld + d + lch * 8;                   \
-        kreg[i] = *(const u32x4 *)kp;                                                \
-        vreg[i] = *(const u32x4 *)(kp + d);                                          \
+    // global -> LDS for a K/V tile, without passing through registers: one wave instruction moves 64 x 16
+    // bytes and lane L's piece lands at the instruction's LDS base + 16 L.  Piece p = 64 (NLD wave + i) + L of
+    // a tile is slot p % CH of key row p / CH; the slot holds logical chunk slot ^ swizzle(row), so the
+    // swizzle is applied on the global side (still whole 16-byte pieces of one row per lane).  The lane part
+    // of the address does not change from tile to tile: the key advance goes into a scalar base.
+    constexpr int NLD = BKV * CH / 256;   // instructions per wave and operand
+    uint32_t kgo[NLD], vgo[NLD];          // byte offsets from the tile's first key row
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int pidx = 64 * (NLD * wave + i) + lane, r = pidx / CH, slot = pidx % CH;
+        kgo[i] = (uint32_t)(r * ld + d + (slot ^ kswz(r)) * 8) * 2u;
+        vgo[i] = (uint32_t)(r * ld + 2 * d + (slot ^ vswz(r)) * 8) * 2u;
     }
+    const uint32_t ks_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)&ks2[0][0];
+    const uint32_t vs_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)&vs2[0][0];
+    auto dma16 = [](uint64_t gbase, uint32_t lane_off, uint32_t lds_off) {
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase), "s"(lds_off) : "memory");
+    };
+    // (the halves go through unsigned 32-bit variables: readfirstlane returns a signed int, which would
+    // sign-extend into the upper half)
+    const uint32_t gb_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)base);
+    const uint32_t gb_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)base >> 32));
+    const uint64_t gbase0 = ((uint64_t)gb_hi << 32) | (uint64_t)gb_lo;
+    auto issue_tile = [&](int k0, int buf) {
+        const uint32_t kdst = ks_lds + (uint32_t)buf * (BKV * CH * 16) + (uint32_t)(NLD * wave) * 1024u;
+        const uint32_t vdst = vs_lds + (uint32_t)buf * (BKV * CH * 16) + (uint32_t)(NLD * wave) * 1024u;
+        if (k0 + BKV <= seq) {
+            const uint64_t gb = gbase0 + (uint64_t)k0 * (uint64_t)ld * 2u;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                dma16(gb, kgo[i], kdst + i * 1024u);
+                dma16(gb, vgo[i], vdst + i * 1024u);
+            }
+        } else {
+            // last, ragged tile of the sequence: key rows past its end re-read the last row (masked as future keys)
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const int pidx = 64 * (NLD * wave + i) + lane, r = pidx / CH, slot = pidx % CH;
+                const int kr = k0 + r < seq ? k0 + r : seq - 1;
+                dma16(gbase0, (uint32_t)(kr * ld + d + (slot ^ kswz(r)) * 8) * 2u, kdst + i * 1024u);
+                dma16(gbase0, (uint32_t)(kr * ld + 2 * d + (slot ^ vswz(r)) * 8) * 2u, vdst + i * 1024u);
+            }
+        }
+    };
     // Transposing LDS read (ds_read_b64_tr_b16): in every group of 16 lanes, lane j hands in the address of
     // four consecutive 16-bit elements ("row j") and lane i gets back element i%4 of rows i/4, i/4+4, i/4+8,
     // i/4+12.  With lane j pointing at key kb + j/4, channels cb + 4 (j%4) .. + 3, lane i receives channel
@@ -115,7 +148,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(cons
         const int key = 4 * fh + tr_key, chan = c * 32 + tr_chan;
         voff[c] = (key * CH + ((chan >> 3) ^ vswz(key))) * 8 + (chan & 7);
     }
-    auto vt_frag = [&](int kb16, int ctile) {                    // keys kb16 + 4 fh + tr_key, kb16 a multiple of 8
+    auto vt_frag = [&](const u32x4 *vs, int kb16, int ctile) {   // keys kb16 + 4 fh + tr_key, kb16 a multiple of 8
         const uint16_t *p = (const uint16_t *)vs + voff[ctile] + kb16 * CH * 8;
         return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16 *)p);
     };
@@ -125,32 +158,56 @@ __global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(cons
 
     const int q_hi = qt * BQ + BQ - 1 < seq - 1 ? qt * BQ + BQ - 1 : seq - 1;   // last query row of the workgroup
     const int n_tiles = q_hi / BKV + 1;
-    ZO_ATTN_LOAD_TILE(0)
+    issue_tile(0, 0);
     for (int t = 0; t < n_tiles; ++t) {
         const int k0 = t * BKV;
-        __syncthreads();                 // previous tile fully consumed
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int r = lrow + RPP * i;
-            ks[r * CH + (lch ^ kswz(r))] = kreg[i];
-            vs[r * CH + (lch ^ vswz(r))] = vreg[i];
-        }
+        const u32x4 *ks = ks2[t & 1];
+        const u32x4 *vs = vs2[t & 1];
+        // this wave's pieces of tile t have landed; after the barrier everybody's have, and everybody is done
+        // with tile t-1, whose buffer the next tile may now overwrite
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        ZO_ATTN_LOAD_TILE(t + 1 < n_tiles ? k0 + BKV : k0)   // prefetch (the last one reloads its own tile, unused)
+        if (t + 1 < n_tiles) issue_tile(k0 + BKV, (t + 1) & 1);
         if (k0 <= q0 + 31) {             // else: tile entirely in this wave's future (uniform per wave)
 
-        // S^T tile: 64 keys x 32 queries = two 32 x 32 accumulators
+        // S^T tile: 64 keys x 32 queries = two 32 x 32 accumulators, advanced in turn so that consecutive
+        // multiplies do not depend on each other.  K fragments run through a ring of four k-steps that is
+        // refilled as it drains: an LDS read is always several multiplies ahead of its use (the
+        // sched_barriers pin that order; left alone the compiler reads each fragment right before it).
+        constexpr int KS = DH / 16, KRING = KS < 4 ? KS : 4;
         f32x16 sacc[2];
+        u32x4 kf[KRING][2];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
+        for (int r = 0; r < KRING; ++r)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
+            for (int kt = 0; kt < 2; ++kt) kf[r][kt] = ks[kt * 32 * CH + koff[r]];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int s = 0; s < DH / 16; ++s) {
-                const u32x4 kf = ks[kt * 32 * CH + koff[s]];
-                sacc[kt] = mfma32<DT>(__builtin_bit_cast(uint4, kf), qf[s], sacc[kt]);
+        for (int s = 0; s < KS; ++s) {
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
+                if (s == 0) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
+                }
+                sacc[kt] = mfma32<DT>(__builtin_bit_cast(uint4, kf[s % KRING][kt]), qf[s], sacc[kt]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (s + KRING < KS) {
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt) kf[s % KRING][kt] = ks[kt * 32 * CH + koff[s + KRING]];
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        // the first V^T fragments are asked for now: they land while the softmax arithmetic runs
+        constexpr int CT = DH / 32;
+        v4i16 vf[2][CT][2];
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            vf[0][c][0] = vt_frag(vs, 0, c);
+            vf[0][c][1] = vt_frag(vs, 8, c);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         // mask (key > query) on the diagonal tiles, tile maximum of the raw scores
         if (k0 + BKV - 1 > q0) {
 #pragma unroll
@@ -199,12 +256,20 @@ __global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(cons
             pf.y = pack2<DT>(sacc[kt][rb + 2], sacc[kt][rb + 3]);
             pf.z = pack2<DT>(sacc[kt][rb + 4], sacc[kt][rb + 5]);
             pf.w = pack2<DT>(sacc[kt][rb + 6], sacc[kt][rb + 7]);
+            if (s + 1 < 4) {                                   // next step's V^T fragments, one step ahead
 #pragma unroll
-            for (int c = 0; c < DH / 32; ++c) {
-                const v4i16 lo = vt_frag(16 * s, c), hi = vt_frag(16 * s + 8, c);
-                const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
+                for (int c = 0; c < CT; ++c) {
+                    vf[(s + 1) & 1][c][0] = vt_frag(vs, 16 * (s + 1), c);
+                    vf[(s + 1) & 1][c][1] = vt_frag(vs, 16 * (s + 1) + 8, c);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                const uint2 lo2 = __builtin_bit_cast(uint2, vf[s & 1][c][0]), hi2 = __builtin_bit_cast(uint2, vf[s & 1][c][1]);
                 oacc[c] = mfma32<DT>(uint4{lo2.x, lo2.y, hi2.x, hi2.y}, pf, oacc[c]);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
         }
     }
@@ -223,8 +288,6 @@ __global__ __launch_bounds__(256, (DH == 64 ? 4 : 2)) void attn_mfma_kernel(cons
             }
     }
 }
-
-#undef ZO_ATTN_LOAD_TILE
 
 }  // namespace
 
