@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(cons
     for (int c = 0; c < DH / 32; ++c)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[c][i] = 0.0f;
-    // running maximum of the raw scores, and the same times log2(e)/sqrt(d_head) (the exponent's offset)
+    // reference maximum of the raw scores (see the key loop), running normaliser; sc = log2(e)/sqrt(d_head)
     float m_run = -INFINITY, l_run = 0.0f;
     const float sc = 1.4426950408889634f / __builtin_sqrtf((float)DH);
 
@@ -167,21 +167,26 @@ __global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(cons
         // with tile t-1, whose buffer the next tile may now overwrite
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        const bool live = k0 <= q0 + 31;  // else: tile entirely in this wave's future (uniform per wave)
+        // the first K fragments are asked for before the next tile's loads are issued: their LDS latency
+        // passes while those instructions go out
+        constexpr int KS = DH / 16, KRING = KS < 4 ? KS : 4;
+        u32x4 kf[KRING][2];
+        if (live) {
+#pragma unroll
+            for (int r = 0; r < KRING; ++r)
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt) kf[r][kt] = ks[kt * 32 * CH + koff[r]];
+        }
+        __builtin_amdgcn_sched_barrier(0);
         if (t + 1 < n_tiles) issue_tile(k0 + BKV, (t + 1) & 1);
-        if (k0 <= q0 + 31) {             // else: tile entirely in this wave's future (uniform per wave)
+        if (live) {
 
         // S^T tile: 64 keys x 32 queries = two 32 x 32 accumulators, advanced in turn so that consecutive
         // multiplies do not depend on each other.  K fragments run through a ring of four k-steps that is
         // refilled as it drains: an LDS read is always several multiplies ahead of its use (the
         // sched_barriers pin that order; left alone the compiler reads each fragment right before it).
-        constexpr int KS = DH / 16, KRING = KS < 4 ? KS : 4;
         f32x16 sacc[2];
-        u32x4 kf[KRING][2];
-#pragma unroll
-        for (int r = 0; r < KRING; ++r)
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt) kf[r][kt] = ks[kt * 32 * CH + koff[r]];
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
 #pragma unroll
@@ -224,9 +229,22 @@ __global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(cons
 #pragma unroll
             for (int i = 0; i < 16; i += 2) tmax = __builtin_fmaxf(__builtin_fmaxf(sacc[kt][i], sacc[kt][i + 1]), tmax);   // three-input maxima
         tmax = __builtin_fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-        const float m_new = __builtin_fmaxf(tmax, m_run);     // finite: key k0 <= q0 <= qrow is never masked
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
-        const float moff = -m_new * sc;
+        // m_run is the reference the exponentials are taken against, not the exact running maximum: it is
+        // raised (and O and the normaliser rescaled) only when some row's scores pass it by more than 2^8 after
+        // scaling, so after the first tiles almost no tile pays for the rescaling.  Probabilities then reach
+        // 2^8 at most; the final division by the normaliser taken against the same reference cancels it.
+        // First tile: m_run = -inf, every row moves (key k0 <= q0 <= qrow is never masked, so tmax is finite).
+        if (__builtin_amdgcn_ballot_w64((tmax - m_run) * sc > 8.0f) != 0) {
+            const float m_new = __builtin_fmaxf(tmax, m_run);
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
+            l_run *= alpha;
+#pragma unroll
+            for (int c = 0; c < DH / 32; ++c)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[c][i] *= alpha;
+            m_run = m_new;
+        }
+        const float moff = -m_run * sc;
         float psum = 0.0f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
@@ -237,15 +255,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(cons
                 psum += p;
             }
         psum += __shfl_xor(psum, 32, 64);
-        l_run = l_run * alpha + psum;
-        // rescale O only when some row's maximum moved (rare after the first tiles)
-        if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
-#pragma unroll
-            for (int c = 0; c < DH / 32; ++c)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[c][i] *= alpha;
-        }
-        m_run = m_new;
+        l_run += psum;
         // O^T += V^T P^T : four contraction steps of 16 keys; lane half h contracts keys 16 s + 4 h + {0..3}
         // and 16 s + 8 + 4 h + {0..3}, the order in which the S^T accumulators hold them
 #pragma unroll
