@@ -78,6 +78,12 @@ __global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(cons
     uint4 qf[DH / 16];
 #pragma unroll
     for (int s = 0; s < DH / 16; ++s) qf[s] = *(const uint4 *)(base + (size_t)qload * ld + s * 16 + fh * 8);
+    // The Q loads are made to land here, before the key loop.  Otherwise the compiler waits for them where the
+    // loop first uses them, by counting outstanding memory operations, and inside the loop that count also
+    // holds the next tile's global->LDS loads (issued from asm, unknown to the compiler): every tile would
+    // wait for its successor's data.
+#pragma unroll
+    for (int s = 0; s < DH / 16; ++s) asm volatile("" ::"v"(qf[s].x), "v"(qf[s].y), "v"(qf[s].z), "v"(qf[s].w));
 
     f32x16 oacc[DH / 32];
 #pragma unroll
