@@ -45,6 +45,17 @@ template <int DT> __device__ __forceinline__ uint32_t pack2(float a, float b)
     else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 
+// The value that the lane 32 places away holds, taken with the register swap between the two halves of a
+// wave (no trip through LDS as a shuffle would make): after the swap of two copies of x, one result holds
+// x of lanes 0..31 in both halves and the other x of lanes 32..63, so one of the two is the lane's own value
+// and the other its partner's; sum and maximum take both and do not care which is which.
+__device__ __forceinline__ void swap_halves(float x, float &a, float &b)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers across the loop
 
@@ -234,7 +245,11 @@ __global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(cons
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int i = 0; i < 16; i += 2) tmax = __builtin_fmaxf(__builtin_fmaxf(sacc[kt][i], sacc[kt][i + 1]), tmax);   // three-input maxima
-        tmax = __builtin_fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        {
+            float ha, hb;
+            swap_halves(tmax, ha, hb);
+            tmax = __builtin_fmaxf(ha, hb);
+        }
         // m_run is the reference the exponentials are taken against, not the exact running maximum: it is
         // raised (and O and the normaliser rescaled) only when some row's scores pass it by more than 2^8 after
         // scaling, so after the first tiles almost no tile pays for the rescaling.  Probabilities then reach
@@ -260,8 +275,11 @@ __global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(cons
                 sacc[kt][i] = p;
                 psum += p;
             }
-        psum += __shfl_xor(psum, 32, 64);
-        l_run += psum;
+        {
+            float ha, hb;
+            swap_halves(psum, ha, hb);
+            l_run += ha + hb;
+        }
         // O^T += V^T P^T : four contraction steps of 16 keys; lane half h contracts keys 16 s + 4 h + {0..3}
         // and 16 s + 8 + 4 h + {0..3}, the order in which the S^T accumulators hold them
 #pragma unroll
