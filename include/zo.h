@@ -215,7 +215,8 @@ int zo_kernel_stage_pm(const void *theta, void *w_plus, void *w_minus, int dtype
  *   epilogue 0: y[.., n] = acc + b           (y in the activation type)
  *            1: y = relu(acc + b)
  *            2: resid += acc + b             (y = resid: fp32, or fp64 for ZO_FP32)
- *            3: y = acc                      (fp32 out, or fp64 for ZO_FP32; bias ignored) */
+ *            3: y = acc                      (fp32 out, or fp64 for ZO_FP32; bias ignored)
+ * 2-byte dtypes: n and k multiples of 8 and every buffer 16-byte aligned (ZO_EINVAL otherwise). */
 int zo_kernel_linear_pm(const void *x, const void *wt_plus, const void *wt_minus,
                         const void *b_plus, const void *b_minus, void *y,
                         int dtype, int m_half, int n, int k, int epilogue, void *stream);

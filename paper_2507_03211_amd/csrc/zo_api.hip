@@ -847,6 +847,9 @@ extern "C" int zo_kernel_linear_pm(const void *x, const void *wt_plus, const voi
     if (epilogue != 3 && (!b_plus || !b_minus)) return fail(ZO_EINVAL, "bias is NULL");
     if (m_half < 1 || n < 1 || k < 1) return fail(ZO_EINVAL, "bad shape");
     if (dtype != ZO_FP32 && (n % 8 || k % 8)) return fail(ZO_EINVAL, "n and k must be multiples of 8 for 2-byte types");
+    if (dtype != ZO_FP32 && ((uintptr_t)x % 16 || (uintptr_t)wt_plus % 16 || (uintptr_t)wt_minus % 16 || (uintptr_t)y % 16 ||
+                             (uintptr_t)b_plus % 16 || (uintptr_t)b_minus % 16))
+        return fail(ZO_EINVAL, "buffers must be 16-byte aligned");
     ZO_HIP(launch_linear(x, wt_plus, wt_minus, b_plus, b_minus, y, dtype, 2, m_half, n, k, epilogue, true, (hipStream_t)stream));
     return ZO_OK;
 }

@@ -258,127 +258,89 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
                                                              int n, int k, int n_sign, int tiles_m, int tiles_n, int total)
 {
     extern __shared__ __attribute__((aligned(16))) uint4 smem[];
-    // XCD-aware renumbering: hardware deals consecutive workgroup ids round-robin to the 8 XCDs.
-    const int per_xcd = (total + 7) / 8;
-    const int lin = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
-    if (lin >= total) return;
-    const int rows_total = n_sign * tiles_m;            // tile-rows over both signs
-    const int band = lin / (kGroupM * tiles_n), rem = lin % (kGroupM * tiles_n);
-    const int band_rows = rows_total - band * kGroupM < kGroupM ? rows_total - band * kGroupM : kGroupM;
-    const int trow = band * kGroupM + rem % band_rows, tcol = rem / band_rows;
-    const int sign = trow / tiles_m, tm_idx = trow % tiles_m;
-
-    const uint16_t *xa = x + (size_t)sign * m_half * k;
-    const uint16_t *wt = sign ? wt_m : wt_p;
-    const uint16_t *bias = sign ? b_m : b_p;
-    const int m0 = tm_idx * BM, n0 = tcol * BN;
+    // Persistent workgroups, one per CU: the hardware deals consecutive workgroup ids round-robin to the 8 XCDs,
+    // so workgroup b sits on XCD b % 8 and is that XCD's slot b / 8; it walks the XCD's contiguous share of the
+    // tile list, slot, slot + slots, ...  The software pipeline does not stop between tiles: while the last two
+    // slabs of a tile are multiplied the first two slabs of the next tile are already being loaded, and they land
+    // during the epilogue.
+    const int per_xcd = (total + 7) / 8, slots = (int)gridDim.x / 8;
+    const int xcd = (int)blockIdx.x % 8, slot0 = (int)blockIdx.x / 8;
+    auto tile_lin = [&](int it) {                                   // -1: no such tile
+        const int sl = slot0 + slots * it, lin = xcd * per_xcd + sl;
+        return (sl < per_xcd && lin < total) ? lin : -1;
+    };
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
+    const int rows_total = n_sign * tiles_m;            // tile-rows over both signs
 
     // Load assignment: one wave instruction moves 8 tile rows x 128 bytes (whole cache lines); wave w,
     // instruction i covers rows (8 w + i) * 8 .. + 7; lane -> (row, 16-byte slot).  The slot holds logical
     // chunk slot ^ (row / 2 mod 8): 16 consecutive rows of one logical chunk then sit on 16 distinct
     // 16-byte positions of the 64-bank (256-byte wide) LDS, so fragment reads are conflict-free.
     const int lrow = lane >> 3, lslot = lane & 7;
-    const uint64_t xbase = uniform64((uint64_t)(uintptr_t)(xa + (size_t)m0 * k));
-    const uint64_t wbase = uniform64((uint64_t)(uintptr_t)(wt + (size_t)n0 * k));
-    uint32_t xg[8], wg[8];                                           // byte offsets from the tile's first row
+    struct Tile {
+        int sign, m0, n0, tcol;
+        uint64_t xbase, wbase;          // first row of the tile in x / in the sign's weights (wave-uniform)
+        uint32_t xg[8], wg[8];          // byte offsets of this lane's 8 + 8 loads from those (clamped at ragged edges)
+    };
+    auto setup = [&](int lin, Tile &t) {
+        const int band = lin / (kGroupM * tiles_n), rem = lin % (kGroupM * tiles_n);
+        const int band_rows = rows_total - band * kGroupM < kGroupM ? rows_total - band * kGroupM : kGroupM;
+        const int trow = band * kGroupM + rem % band_rows;
+        t.tcol = rem / band_rows;
+        t.sign = trow / tiles_m;
+        t.m0 = (trow % tiles_m) * BM;
+        t.n0 = t.tcol * BN;
+        const uint16_t *xa = x + (size_t)t.sign * m_half * k;
+        const uint16_t *wt = t.sign ? wt_m : wt_p;
+        t.xbase = uniform64((uint64_t)(uintptr_t)(xa + (size_t)t.m0 * k));
+        t.wbase = uniform64((uint64_t)(uintptr_t)(wt + (size_t)t.n0 * k));
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int row = (wave * 8 + i) * 8 + lrow;
-        const int chunk = lslot ^ ((row >> 1) & 7);
-        int xr = m0 + row; xr = xr < m_half ? xr : m_half - 1;       // clamp: masked at the store
-        int wr = n0 + row; wr = wr < n ? wr : n - 1;
-        xg[i] = ((uint32_t)(xr - m0) * (uint32_t)k + chunk * 8) * 2u;
-        wg[i] = ((uint32_t)(wr - n0) * (uint32_t)k + chunk * 8) * 2u;
-    }
+        for (int i = 0; i < 8; ++i) {
+            const int row = (wave * 8 + i) * 8 + lrow;
+            const int chunk = lslot ^ ((row >> 1) & 7);
+            int xr = t.m0 + row; xr = xr < m_half ? xr : m_half - 1;       // clamp: masked at the store
+            int wr = t.n0 + row; wr = wr < n ? wr : n - 1;
+            t.xg[i] = ((uint32_t)(xr - t.m0) * (uint32_t)k + chunk * 8) * 2u;
+            t.wg[i] = ((uint32_t)(wr - t.n0) * (uint32_t)k + chunk * 8) * 2u;
+        }
+    };
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
-    const int nk = k / BK;
-    // x slab t lives in x stage t % 3, w slab t in w stage t % 2 (after the three x stages)
-    auto x_stage = [&](int t) { return lds_base + (uint32_t)(t % STX) * (kTileU4 * 16) + (uint32_t)wave * 8192u; };
-    auto w_stage = [&](int t) { return lds_base + (uint32_t)(STX + t % STW) * (kTileU4 * 16) + (uint32_t)wave * 8192u; };
-    auto k_of = [&](int t) { return (t < nk ? t : nk - 1) * BK; };      // past the end: reload the last slab (never multiplied)
-    auto issue_x = [&](int t) {
-        const uint64_t b = xbase + 2u * (uint32_t)k_of(t);
-        const uint32_t st = x_stage(t);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) gload_lds16(b, xg[i], st + i * 1024u);
-    };
-    auto issue_w = [&](int t) {
-        const uint64_t b = wbase + 2u * (uint32_t)k_of(t);
-        const uint32_t st = w_stage(t);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) gload_lds16(b, wg[i], st + i * 1024u);
-    };
+    const int nk = k / BK;                              // >= 3 (the launcher sees to it)
+    // Slabs are numbered through all the tiles of this workgroup (slab g of tile number it, k-slab kt: g = it nk + kt).
+    // x slab g lives in x stage g % 3, w slab g in w stage g % 2 (after the three x stages).
+    auto x_stage = [&](int g) { return lds_base + (uint32_t)(g % STX) * (kTileU4 * 16) + (uint32_t)wave * 8192u; };
+    auto w_stage = [&](int g) { return lds_base + (uint32_t)(STX + g % STW) * (kTileU4 * 16) + (uint32_t)wave * 8192u; };
 
     f32x16 acc[4][4];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
-
     const int fr = lane & 31, fh = lane >> 5, sw = (fr >> 1) & 7;
     const int xrow = (wm * 128 + fr) * 8, wrow = (wn * 128 + fr) * 8;     // uint4 index of the lane's first rows
     uint4 wfa[4], xfa[4], wfb[4], xfb[4];                                 // two fragment sets: one multiplies while one loads
-    auto load_frags = [&](int slab, int ks, uint4 (&wf)[4], uint4 (&xf)[4]) {
-        const uint4 *xs = smem + (slab % STX) * kTileU4;
-        const uint4 *ws = smem + (STX + slab % STW) * kTileU4;
-        const int slot = (2 * ks + fh) ^ sw;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            wf[t] = ws[wrow + t * 256 + slot];
-            xf[t] = xs[xrow + t * 256 + slot];
-        }
-    };
-    auto mma16 = [&](const uint4 (&wf)[4], const uint4 (&xf)[4]) {
-#pragma unroll
-        for (int tn = 0; tn < 4; ++tn)
-#pragma unroll
-            for (int tm = 0; tm < 4; ++tm) acc[tn][tm] = mfma32<DT>(wf[tn], xf[tm], acc[tn][tm]);
-    };
-
-    // One fragment of set (wf, xf) for k-step ks of a slab, in the order the multiplies need them:
+    // One fragment of set (wf, xf) for k-step ks of slab g, in the order the multiplies need them:
     // wf0, xf0, xf1, xf2, xf3, wf1, wf2, wf3.
-    auto frag1 = [&](int slab, int ks, int idx, uint4 (&wf)[4], uint4 (&xf)[4]) {
-        const uint4 *xs = smem + (slab % STX) * kTileU4;
-        const uint4 *ws = smem + (STX + slab % STW) * kTileU4;
+    auto frag1 = [&](int g, int ks, int idx, uint4 (&wf)[4], uint4 (&xf)[4]) {
+        const uint4 *xs = smem + (g % STX) * kTileU4;
+        const uint4 *ws = smem + (STX + g % STW) * kTileU4;
         const int slot = (2 * ks + fh) ^ sw;
         if (idx == 0) wf[0] = ws[wrow + slot];
         else if (idx <= 4) xf[idx - 1] = xs[xrow + (idx - 1) * 256 + slot];
         else wf[idx - 4] = ws[wrow + (idx - 4) * 256 + slot];
     };
-
-    // Software pipeline.  The 160 KiB of LDS hold three stages of the activation tile and two of the weight
-    // tile, so half of every slab's loads are issued two slab-times ahead and only the other half one ahead:
-    // with a single slab of lookahead for everything the multiplies wait on memory latency.  One wave per SIMD
-    // means nothing else hides an instruction that is slow to issue, so neither the global->LDS loads nor the
-    // LDS fragment reads come in bursts: each sits alone between two multiplies and issues while the matrix
-    // pipe works on the one before.  The fragments of a quarter slab (16 multiplies) are read during the quarter
-    // before it, into the set of registers the quarter before that used.  The barrier sits in the middle of
-    // the third quarter, once this wave's last LDS reads of slab kt are in registers.
-    // sched_barrier(0) pins the order (the compiler would sink each LDS read down to its first use).
-    issue_x(0);
-    issue_w(0);
-    issue_x(1);
-    issue_w(1);
-    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");               // slab 0 landed
-    __builtin_amdgcn_s_barrier();
-    load_frags(0, 0, wfa, xfa);
     // Multiplies j0 .. j1-1 of the 4 x 4 fragment product of set (wf, xf).  Before multiply j:
-    //  * fragments rper (j - rj0) / revery .. + rper - 1 of set (nwf, nxf) are read for k-step nks of slab nslab,
+    //  * fragments rper (j - rj0) / revery .. + rper - 1 of set (nwf, nxf) are read for k-step nks of slab ng,
     //    when that divides;
-    //  * load lfirst + (j - lj0) / levery (lane offsets `offs` from the scalar base `gbase`) goes out into LDS at `st`, when that divides, `nload` in all.
-    auto mma_rl = [&](const uint4 (&wf)[4], const uint4 (&xf)[4], int j0, int j1, uint4 (&nwf)[4], uint4 (&nxf)[4], int nslab,
+    //  * load lfirst + (j - lj0) / levery (lane offsets `offs` from the scalar base `gbase`) goes out into LDS at
+    //    `st`, when that divides, `nload` in all.
+    //  `first`: the product starts the accumulators (first quarter of a tile's first slab) instead of adding to them.
+    auto mma_rl = [&](const uint4 (&wf)[4], const uint4 (&xf)[4], int j0, int j1, uint4 (&nwf)[4], uint4 (&nxf)[4], int ng,
                       int nks, int rj0, int revery, int rper, const uint32_t (&offs)[8], uint64_t gbase, uint32_t st,
-                      int lfirst, int nload, int lj0, int levery) {
+                      int lfirst, int nload, int lj0, int levery, bool first = false) {
 #pragma unroll
         for (int j = j0; j < j1; ++j) {
             if (j >= rj0 && (j - rj0) % revery == 0 && (j - rj0) / revery * rper < 8) {
 #pragma unroll
-                for (int r = 0; r < rper; ++r) frag1(nslab, nks, (j - rj0) / revery * rper + r, nwf, nxf);
+                for (int r = 0; r < rper; ++r) frag1(ng, nks, (j - rj0) / revery * rper + r, nwf, nxf);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (j >= lj0 && (j - lj0) % levery == 0 && (j - lj0) / levery < nload) {
@@ -386,151 +348,231 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
                 gload_lds16(gbase, offs[q], st + q * 1024u);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            acc[j >> 2][j & 3] = mfma32<DT>(wf[j >> 2], xf[j & 3], acc[j >> 2][j & 3]);
+            if (first) {
+                f32x16 zero;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
+                acc[j >> 2][j & 3] = mfma32<DT>(wf[j >> 2], xf[j & 3], zero);
+            } else {
+                acc[j >> 2][j & 3] = mfma32<DT>(wf[j >> 2], xf[j & 3], acc[j >> 2][j & 3]);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    for (int kt = 0; kt < nk; ++kt) {
-        // x(kt+2) goes into the activation stage that slab kt-1 left at the previous barrier: its 8 loads sit
-        // under the 40 multiplies before this slab's barrier; w(kt+2) can only follow the barrier: its 8 loads
-        // sit under the 24 multiplies after it.
-        const uint64_t kx = xbase + 2u * (uint32_t)k_of(kt + 2), kw = wbase + 2u * (uint32_t)k_of(kt + 2);
-        const uint32_t stx = x_stage(kt + 2), stw = w_stage(kt + 2);
-        mma_rl(wfa, xfa, 0, 16, wfb, xfb, kt, 1, 1, 2, 1, xg, kx, stx, 0, 3, 0, 6);
-        mma_rl(wfb, xfb, 0, 16, wfa, xfa, kt, 2, 1, 2, 1, xg, kx, stx, 3, 3, 0, 6);
-        // the last fragments of slab kt, two reads at a time, so that they have landed when the barrier's wait comes
-        mma_rl(wfa, xfa, 0, 8, wfb, xfb, kt, 3, 0, 1, 2, xg, kx, stx, 6, 2, 4, 2);
-        // slab kt+1 landed (only x(kt+2), the 8 newest loads, may still be out); slab kt fully in registers
+    // Software pipeline.  The 160 KiB of LDS hold three stages of the activation tile and two of the weight
+    // tile, so half of every slab's loads are issued two slab-times ahead and only the other half one ahead:
+    // with a single slab of lookahead for everything the multiplies wait on memory latency.  One wave per SIMD
+    // means nothing else hides an instruction that is slow to issue, so neither the global->LDS loads nor the
+    // LDS fragment reads come in bursts: each sits alone between two multiplies and issues while the matrix
+    // pipe works on the one before.  The fragments of a quarter slab (16 multiplies) are read during the quarter
+    // before it, into the set of registers the quarter before that used.  The barrier sits in the middle of
+    // the third quarter, once this wave's last LDS reads of slab g are in registers.
+    // sched_barrier(0) pins the order (the compiler would sink each LDS read down to its first use).
+    //
+    // One slab: multiplies slab g (fragment set A holds its first quarter), loads slab g + 2 from (xb, wb) with
+    // the lane offsets (xo, wo).  x(g+2) goes into the activation stage that slab g-1 left at the previous barrier:
+    // its 8 loads sit under the 40 multiplies before this slab's barrier; w(g+2) can only follow the barrier: its
+    // 8 loads sit under the 24 multiplies after it.
+    auto slab = [&](int g, uint64_t xb, uint64_t wb, const uint32_t (&xo)[8], const uint32_t (&wo)[8], bool first) {
+        const uint32_t stx = x_stage(g + 2), stw = w_stage(g + 2);
+        mma_rl(wfa, xfa, 0, 16, wfb, xfb, g, 1, 1, 2, 1, xo, xb, stx, 0, 3, 0, 6, first);
+        mma_rl(wfb, xfb, 0, 16, wfa, xfa, g, 2, 1, 2, 1, xo, xb, stx, 3, 3, 0, 6);
+        // the last fragments of slab g, two reads at a time, so that they have landed when the barrier's wait comes
+        mma_rl(wfa, xfa, 0, 8, wfb, xfb, g, 3, 0, 1, 2, xo, xb, stx, 6, 2, 4, 2);
+        // slab g+1 landed (only x(g+2), the 8 newest loads, may still be out); slab g fully in registers
         asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        mma_rl(wfa, xfa, 8, 16, wfb, xfb, kt, 3, 99, 1, 1, wg, kw, stw, 0, 3, 8, 3);
-        // the first fragments of slab kt+1 early in the quarter: the loop's back edge waits for all LDS reads.
-        // Past the end these are fragments of a reloaded slab, never multiplied
-        mma_rl(wfb, xfb, 0, 16, wfa, xfa, kt + 1, 0, 0, 1, 1, wg, kw, stw, 3, 5, 0, 3);
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // drain the tail loads before LDS is released
-
-    if constexpr (EPI == 4) {
-        const int n_partial = 2 * tiles_n;
-#pragma unroll
-        for (int tm = 0; tm < 4; ++tm) {
-            const int mr = m0 + wm * 128 + tm * 32 + fr;
-            const size_t row = (size_t)sign * m_half + (mr < m_half ? mr : m_half - 1);
-            const f32x16 a[4] = {acc[0][tm], acc[1][tm], acc[2][tm], acc[3][tm]};
-            float dummy_logit;
-            float2 dummy_pair;
-            const bool live = mr < m_half;
-            ce_partial_row<4>(a, n0 + wn * 128, fh, n, live ? ((const int32_t *)b_p)[row] : -1,
-                              live ? (float *)b_m + row : &dummy_logit,
-                              live ? (float2 *)y + row * n_partial + (tcol * 2 + wn) : &dummy_pair);
-        }
-        return;
-    }
-    // Output through LDS so that global stores are whole rows: in the MFMA layout a lane holds runs of 4
-    // consecutive columns of ONE row and a wave instruction would touch 32 rows with 16 or 32 bytes each.
-    // Every wave stages 32 rows x 128 columns at a time in a region of its own (no workgroup barrier inside),
-    // XOR-swizzled so that both the run-wise writes and the row-wise 16-byte reads are free of bank conflicts.
-    __syncthreads();                                                 // every wave is done with the operand stages
-    constexpr bool kOut16 = (EPI == 0 || EPI == 1);                  // 2-byte outputs; else fp32
-    char *stage = (char *)smem + wave * 16384;
-    const int ncol0 = n0 + wn * 128;
-    // Bias: 2-byte outputs take it before the rounding, so per run of the MFMA layout (the same 16 runs for
-    // every tm); fp32 outputs take it after the LDS pass, where a lane always holds the same 4 columns.
-    float bvals[kOut16 ? 4 : 1][4][4];
-#pragma unroll
-    for (int tn = 0; tn < (kOut16 ? 4 : 0); ++tn)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int nc = ncol0 + tn * 32 + 8 * g + 4 * fh;
-            uint2 braw = uint2{0u, 0u};
-            if (nc < n) braw = *(const uint2 *)(bias + nc);
-            bvals[tn][g][0] = Prec<DT>::w2f((uint16_t)(braw.x & 0xffff));
-            bvals[tn][g][1] = Prec<DT>::w2f((uint16_t)(braw.x >> 16));
-            bvals[tn][g][2] = Prec<DT>::w2f((uint16_t)(braw.y & 0xffff));
-            bvals[tn][g][3] = Prec<DT>::w2f((uint16_t)(braw.y >> 16));
-        }
-    // Residual epilogue: the 16 reads of the running sum that a pass needs are all issued one pass ahead, so a
-    // tile pays the memory latency once and not once per row group (a load may not overtake an earlier store
-    // that the compiler cannot tell apart from it).
-    float4 hres[2][16];
-    auto load_res = [&](int tm, float4 (&h)[16]) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int r = 2 * i + (lane >> 5), c = lane & 31;
-            const int mr = m0 + wm * 128 + tm * 32 + r, nc = ncol0 + c * 4;
-            h[i] = float4{0.f, 0.f, 0.f, 0.f};
-            if (mr < m_half && nc < n) h[i] = *(const float4 *)((const float *)y + ((size_t)sign * m_half + mr) * n + nc);
-        }
+        mma_rl(wfa, xfa, 8, 16, wfb, xfb, g, 3, 99, 1, 1, wo, wb, stw, 0, 3, 8, 3);
+        // the first fragments of slab g+1 early in the quarter: the loop's back edge waits for all LDS reads
+        mma_rl(wfb, xfb, 0, 16, wfa, xfa, g + 1, 0, 0, 1, 1, wo, wb, stw, 3, 5, 0, 3);
     };
-    float bias4[4] = {0.f, 0.f, 0.f, 0.f};
-    if constexpr (EPI == 2) {
-        load_res(0, hres[0]);
-        const int nc = ncol0 + (lane & 31) * 4;
-        if (nc < n) {
-            const uint2 braw = *(const uint2 *)(bias + nc);
-            bias4[0] = Prec<DT>::w2f((uint16_t)(braw.x & 0xffff));
-            bias4[1] = Prec<DT>::w2f((uint16_t)(braw.x >> 16));
-            bias4[2] = Prec<DT>::w2f((uint16_t)(braw.y & 0xffff));
-            bias4[3] = Prec<DT>::w2f((uint16_t)(braw.y >> 16));
+
+    Tile cur, nxt;
+    int lin = tile_lin(0);
+    if (lin < 0) return;
+    setup(lin, cur);
+    int it = 0, g0 = 0;                                 // tile number of this workgroup, its first slab
+    // prologue of the first tile only: slabs 0 and 1, fragments of the first quarter
+#pragma unroll
+    for (int i = 0; i < 8; ++i) gload_lds16(cur.xbase, cur.xg[i], x_stage(0) + i * 1024u);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) gload_lds16(cur.wbase, cur.wg[i], w_stage(0) + i * 1024u);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) gload_lds16(cur.xbase + 2u * BK, cur.xg[i], x_stage(1) + i * 1024u);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) gload_lds16(cur.wbase + 2u * BK, cur.wg[i], w_stage(1) + i * 1024u);
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");               // slab 0 landed
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int idx = 0; idx < 8; ++idx) frag1(0, 0, idx, wfa, xfa);
+
+    for (;;) {
+        const int lin_next = tile_lin(it + 1);
+        const bool has_next = lin_next >= 0;
+        if (has_next) {
+            setup(lin_next, nxt);
+        } else {
+            // no successor: the two slabs loaded ahead are this tile's last two over again, which nothing reads
+            nxt = cur;
+            nxt.xbase += 2u * (uint32_t)((nk - 2) * BK);
+            nxt.wbase += 2u * (uint32_t)((nk - 2) * BK);
         }
-    }
+        // all slabs but the last two load two slabs ahead in this tile; the first one starts the accumulators
+        slab(g0, cur.xbase + 2u * (uint32_t)(2 * BK), cur.wbase + 2u * (uint32_t)(2 * BK), cur.xg, cur.wg, true);
+        for (int kt = 1; kt < nk - 2; ++kt)
+            slab(g0 + kt, cur.xbase + 2u * (uint32_t)((kt + 2) * BK), cur.wbase + 2u * (uint32_t)((kt + 2) * BK), cur.xg, cur.wg, false);
+        // the last two load the first two slabs of the next tile
+        slab(g0 + nk - 2, nxt.xbase, nxt.wbase, nxt.xg, nxt.wg, false);
+        slab(g0 + nk - 1, nxt.xbase + 2u * BK, nxt.wbase + 2u * BK, nxt.xg, nxt.wg, false);
+        const int g_last = g0 + nk - 1;
+
+        // ---- epilogue of tile `cur`
+        const int sign = cur.sign, m0 = cur.m0, n0 = cur.n0;
+        const uint16_t *bias = sign ? b_m : b_p;
+        if constexpr (EPI == 4) {
+            const int n_partial = 2 * tiles_n;
 #pragma unroll
-    for (int tm = 0; tm < 4; ++tm) {
-        if constexpr (EPI == 2) {
-            if (tm < 3) load_res(tm + 1, hres[(tm + 1) & 1]);
-        }
-#pragma unroll
-        for (int tn = 0; tn < 4; ++tn)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v[e] = acc[tn][tm][4 * g + e];
-                    if constexpr (kOut16) v[e] += bvals[tn][g][e];
-                    if constexpr (EPI == 1) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
-                }
-                const int run = tn * 8 + 2 * g + fh;                 // which run of 4 columns (0..31) of the row
-                if constexpr (kOut16) {
-                    uint2 o;
-                    o.x = (uint32_t)Prec<DT>::acc2a(v[0]) | ((uint32_t)Prec<DT>::acc2a(v[1]) << 16);
-                    o.y = (uint32_t)Prec<DT>::acc2a(v[2]) | ((uint32_t)Prec<DT>::acc2a(v[3]) << 16);
-                    *(uint2 *)(stage + fr * 256 + ((run ^ fr) << 3)) = o;          // 8-byte slots, XOR by the row
-                } else {
-                    *(float4 *)(stage + fr * 512 + ((run ^ (fr & 15)) << 4)) = float4{v[0], v[1], v[2], v[3]};
-                }
-            }
-        const int mbase = m0 + wm * 128 + tm * 32;
-        asm volatile("" ::: "memory");          // the wave's LDS operations execute in order; keep the compiler to it too
-        if constexpr (kOut16) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int r = 4 * i + (lane >> 4), c16 = lane & 15;               // 16 lanes x 16 bytes = one 256-byte row
-                uint4 q = *(const uint4 *)(stage + r * 256 + ((c16 ^ (r >> 1)) << 4));
-                if (r & 1) q = uint4{q.z, q.w, q.x, q.y};                        // odd rows hold the two runs swapped
-                const int mr = mbase + r, nc = ncol0 + c16 * 8;
-                if (mr < m_half && nc < n) *(uint4 *)((uint16_t *)y + ((size_t)sign * m_half + mr) * n + nc) = q;
+            for (int tm = 0; tm < 4; ++tm) {
+                const int mr = m0 + wm * 128 + tm * 32 + fr;
+                const size_t row = (size_t)sign * m_half + (mr < m_half ? mr : m_half - 1);
+                const f32x16 a[4] = {acc[0][tm], acc[1][tm], acc[2][tm], acc[3][tm]};
+                float dummy_logit;
+                float2 dummy_pair;
+                const bool live = mr < m_half;
+                ce_partial_row<4>(a, n0 + wn * 128, fh, n, live ? ((const int32_t *)b_p)[row] : -1,
+                                  live ? (float *)b_m + row : &dummy_logit,
+                                  live ? (float2 *)y + row * n_partial + (cur.tcol * 2 + wn) : &dummy_pair);
             }
         } else {
+            // Output through LDS so that global stores are whole rows: in the MFMA layout a lane holds runs of 4
+            // consecutive columns of ONE row and a wave instruction would touch 32 rows with 16 or 32 bytes each.
+            // A wave stages 8 KiB at a time (32 rows x 128 two-byte columns, or 16 rows of fp32) in its own slice
+            // of the activation stage that the tile's last slab has just left: every wave finished reading that
+            // stage before the slab's barrier, and the next loads into the slice are this wave's own, issued after
+            // the epilogue.  No workgroup barrier.  XOR-swizzled so that both the run-wise writes and the row-wise
+            // 16-byte reads are free of bank conflicts.
+            constexpr bool kOut16 = (EPI == 0 || EPI == 1);              // 2-byte outputs; else fp32
+            constexpr int RP = kOut16 ? 32 : 16;                         // rows per pass
+            constexpr int NPASS = 128 / RP;
+            char *stage = (char *)smem + (size_t)(g_last % STX) * (kTileU4 * 16) + wave * 8192;
+            const int ncol0 = n0 + wn * 128;
+            // Bias: 2-byte outputs take it before the rounding, so per run of the MFMA layout (the same 16 runs
+            // for every row block); fp32 outputs take it after the LDS pass, where a lane always holds the same
+            // 4 columns.
+            // They come through the scalar cache (a wave-uniform address in the constant address space: 16 bytes
+            // = the 8 columns of a run pair, of which the lane half keeps its 4): a vector load here would make
+            // the compiler wait for every outstanding vector memory operation, the next tile's loads included.
+            float bvals[kOut16 ? 4 : 1][4][4];
+            if constexpr (kOut16) {
+                typedef const __attribute__((address_space(4))) u32x4 *cptr;
+                const uint64_t bbase = uniform64((uint64_t)(uintptr_t)bias);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int r = 2 * i + (lane >> 5), c = lane & 31;                 // 32 lanes x 16 bytes = one 512-byte row
-                const float4 q = *(const float4 *)(stage + r * 512 + ((c ^ (r & 15)) << 4));
-                const int mr = mbase + r, nc = ncol0 + c * 4;
-                if (mr < m_half && nc < n) {
-                    float4 *p = (float4 *)((float *)y + ((size_t)sign * m_half + mr) * n + nc);
-                    if constexpr (EPI == 2) {
-                        float4 h = hres[tm & 1][i];
-                        h.x += q.x + bias4[0]; h.y += q.y + bias4[1]; h.z += q.z + bias4[2]; h.w += q.w + bias4[3];
-                        *p = h;
-                    } else {
-                        *p = q;
+                for (int tn = 0; tn < 4; ++tn)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        int c8 = ncol0 + tn * 32 + 8 * g;               // wave-uniform; clamped: columns >= n are never stored
+                        c8 = c8 + 8 <= n ? c8 : n - 8;
+                        const u32x4 raw = *(cptr)(uintptr_t)(bbase + 2u * (uint32_t)c8);
+                        const uint32_t lo = fh ? raw.z : raw.x, hi = fh ? raw.w : raw.y;
+                        bvals[tn][g][0] = Prec<DT>::w2f((uint16_t)(lo & 0xffff));
+                        bvals[tn][g][1] = Prec<DT>::w2f((uint16_t)(lo >> 16));
+                        bvals[tn][g][2] = Prec<DT>::w2f((uint16_t)(hi & 0xffff));
+                        bvals[tn][g][3] = Prec<DT>::w2f((uint16_t)(hi >> 16));
                     }
+            }
+            // Residual epilogue: the 8 reads of the running sum that a pass needs are all issued one pass ahead,
+            // so a tile pays the memory latency once and not once per row group (a load may not overtake an
+            // earlier store that the compiler cannot tell apart from it).
+            float4 hres[2][8];
+            auto load_res = [&](int pass, float4 (&h)[8]) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int r = 2 * i + (lane >> 5), c = lane & 31;
+                    const int mr = m0 + wm * 128 + pass * 16 + r, nc = ncol0 + c * 4;
+                    h[i] = float4{0.f, 0.f, 0.f, 0.f};
+                    if (mr < m_half && nc < n) h[i] = *(const float4 *)((const float *)y + ((size_t)sign * m_half + mr) * n + nc);
+                }
+            };
+            float bias4[4] = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (EPI == 2) {
+                load_res(0, hres[0]);
+                const int nc = ncol0 + (lane & 31) * 4;
+                if (nc < n) {
+                    const uint2 braw = *(const uint2 *)(bias + nc);
+                    bias4[0] = Prec<DT>::w2f((uint16_t)(braw.x & 0xffff));
+                    bias4[1] = Prec<DT>::w2f((uint16_t)(braw.x >> 16));
+                    bias4[2] = Prec<DT>::w2f((uint16_t)(braw.y & 0xffff));
+                    bias4[3] = Prec<DT>::w2f((uint16_t)(braw.y >> 16));
                 }
             }
+#pragma unroll
+            for (int pass = 0; pass < NPASS; ++pass) {
+                const int tm = pass * RP / 32;                          // MFMA row block of this pass
+                if constexpr (EPI == 2) {
+                    if (pass + 1 < NPASS) load_res(pass + 1, hres[(pass + 1) & 1]);
+                }
+                // fp32: the pass covers rows 16 (pass % 2) .. + 15 of the block, held by the lanes with that fr / 16
+                if (kOut16 || (fr >> 4) == (pass & 1)) {
+#pragma unroll
+                    for (int tn = 0; tn < 4; ++tn)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            float v[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                v[e] = acc[tn][tm][4 * g + e];
+                                if constexpr (kOut16) v[e] += bvals[tn][g][e];
+                                if constexpr (EPI == 1) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+                            }
+                            const int run = tn * 8 + 2 * g + fh;         // which run of 4 columns (0..31) of the row
+                            if constexpr (kOut16) {
+                                uint2 o;
+                                o.x = (uint32_t)Prec<DT>::acc2a(v[0]) | ((uint32_t)Prec<DT>::acc2a(v[1]) << 16);
+                                o.y = (uint32_t)Prec<DT>::acc2a(v[2]) | ((uint32_t)Prec<DT>::acc2a(v[3]) << 16);
+                                *(uint2 *)(stage + fr * 256 + ((run ^ fr) << 3)) = o;      // 8-byte slots, XOR by the row
+                            } else {
+                                *(float4 *)(stage + (fr & 15) * 512 + ((run ^ (fr & 15)) << 4)) = float4{v[0], v[1], v[2], v[3]};
+                            }
+                        }
+                }
+                const int mbase = m0 + wm * 128 + pass * RP;
+                asm volatile("" ::: "memory");      // the wave's LDS operations execute in order; keep the compiler to it too
+                if constexpr (kOut16) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int r = 4 * i + (lane >> 4), c16 = lane & 15;           // 16 lanes x 16 bytes = one 256-byte row
+                        uint4 q = *(const uint4 *)(stage + r * 256 + ((c16 ^ (r >> 1)) << 4));
+                        if (r & 1) q = uint4{q.z, q.w, q.x, q.y};                    // odd rows hold the two runs swapped
+                        const int mr = mbase + r, nc = ncol0 + c16 * 8;
+                        if (mr < m_half && nc < n) *(uint4 *)((uint16_t *)y + ((size_t)sign * m_half + mr) * n + nc) = q;
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int r = 2 * i + (lane >> 5), c = lane & 31;             // 32 lanes x 16 bytes = one 512-byte row
+                        const float4 q = *(const float4 *)(stage + r * 512 + ((c ^ r) << 4));
+                        const int mr = mbase + r, nc = ncol0 + c * 4;
+                        if (mr < m_half && nc < n) {
+                            float4 *p = (float4 *)((float *)y + ((size_t)sign * m_half + mr) * n + nc);
+                            if constexpr (EPI == 2) {
+                                float4 h = hres[pass & 1][i];
+                                h.x += q.x + bias4[0]; h.y += q.y + bias4[1]; h.z += q.z + bias4[2]; h.w += q.w + bias4[3];
+                                *p = h;
+                            } else {
+                                *p = q;
+                            }
+                        }
+                    }
+                }
+                asm volatile("" ::: "memory");
+            }
         }
-        asm volatile("" ::: "memory");
+        if (!has_next) break;
+        cur = nxt;
+        g0 += nk;
+        ++it;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // the tail loads land before LDS is released
 }
 
 }  // namespace big
@@ -559,7 +601,17 @@ hipError_t launch_big_t(const void *x, const void *wt_p, const void *wt_m, const
 {
     const int tiles_m = (m_half + big::BM - 1) / big::BM, tiles_n = (n + big::BN - 1) / big::BN;
     const int total = n_sign * tiles_m * tiles_n;
-    const dim3 grid((total + 7) / 8 * 8), block(256);
+    // persistent workgroups: one per CU (the 160 KiB of LDS allow no second one), a multiple of the 8 XCDs
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, v = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        n_cu = v >= 8 ? v / 8 * 8 : 8;
+    }
+    const int want = (total + 7) / 8 * 8;
+    const dim3 grid(want < n_cu ? want : n_cu), block(256);
 #define ZO_B(E)                                                                                                                  \
     {                                                                                                                            \
         auto kern = big::linear_mfma256_kernel<DT, E>;                                                                           \
@@ -587,7 +639,7 @@ hipError_t launch_big_t(const void *x, const void *wt_p, const void *wt_m, const
 // The big tiling pays once there are enough 256-tiles to keep 256 CUs busy.
 bool use_big(int n_sign, int m_half, int n, int k)
 {
-    if (k % big::BK) return false;
+    if (k % big::BK || k < 3 * big::BK) return false;      // the pipeline runs two slabs ahead, and the first slab of a tile is special
     const long tiles = (long)n_sign * ((m_half + big::BM - 1) / big::BM) * ((n + big::BN - 1) / big::BN);
     return tiles >= 384;
 }
@@ -605,6 +657,9 @@ hipError_t launch_linear_mfma(const void *x, const void *wt_p, const void *wt_m,
                               int dtype, int n_sign, int m_half, int n, int k, int epilogue, hipStream_t s)
 {
     if (!mfma_linear_supported(m_half, n, k) || (dtype != kBF16 && dtype != kFP16)) return hipErrorInvalidValue;
+    // 16-byte pieces everywhere (operand loads, row-wise stores, bias through the scalar cache)
+    if ((uintptr_t)x % 16 || (uintptr_t)wt_p % 16 || (uintptr_t)wt_m % 16 || (uintptr_t)y % 16) return hipErrorInvalidValue;
+    if (epilogue != 3 && epilogue != 4 && ((uintptr_t)b_p % 16 || (uintptr_t)b_m % 16)) return hipErrorInvalidValue;
     if (use_big(n_sign, m_half, n, k)) {
         return dtype == kBF16 ? launch_big_t<kBF16>(x, wt_p, wt_m, b_p, b_m, y, n_sign, m_half, n, k, epilogue, s)
                               : launch_big_t<kFP16>(x, wt_p, wt_m, b_p, b_m, y, n_sign, m_half, n, k, epilogue, s);
