@@ -636,12 +636,13 @@ hipError_t launch_big_t(const void *x, const void *wt_p, const void *wt_m, const
     return hipGetLastError();
 }
 
-// The big tiling pays once there are enough 256-tiles to keep 256 CUs busy.
+// The big tiling pays once its tiles occupy about half of the 256 CUs: measured at 192 tiles it is 1.5 times as
+// fast as the small tiling although a quarter of the CUs idle.
 bool use_big(int n_sign, int m_half, int n, int k)
 {
     if (k % big::BK || k < 3 * big::BK) return false;      // the pipeline runs two slabs ahead, and the first slab of a tile is special
     const long tiles = (long)n_sign * ((m_half + big::BM - 1) / big::BM) * ((n + big::BN - 1) / big::BN);
-    return tiles >= 384;
+    return tiles >= 128;
 }
 
 }  // namespace
