@@ -52,11 +52,14 @@ def test_layernorm(dtype, m_half, d):
 
 @pytest.mark.parametrize("dtype", [zi.FP32, zi.BF16, zi.FP16])
 @pytest.mark.parametrize("m_half,n,k", [(64, 128, 64), (130, 200, 192), (37, 72, 128), (256, 384, 320), (3, 8, 24),
-                                        (2100, 2600, 128), (1024, 8200, 64)])
+                                        (2100, 2600, 128), (1024, 8200, 64),
+                                        (2100, 2600, 192), (1024, 8200, 256), (1280, 3328, 192), (2100, 4104, 320)])
 @pytest.mark.parametrize("epi", [0, 1, 2, 3])
 def test_linear_pm(dtype, m_half, n, k, epi):
-    """Shapes span several 128-wide tiles with ragged tails; (3, 8, 24) is below the MFMA tile depth; the last
-    two have enough 256-wide tiles (ragged in both directions) to take the 256 x 256 x 32 direct-to-LDS kernel."""
+    """Shapes span several 128-wide tiles with ragged tails; (3, 8, 24) is below the MFMA tile depth.  The last
+    four take the persistent 256 x 256 kernel (at least 128 tiles, k >= 192), ragged in both directions: 198 tiles
+    on 200 workgroups (two find no tile), 264 tiles on 256 workgroups (some walk two tiles), 130 whole tiles, and
+    306 tiles with five slabs each."""
     rng = np.random.Generator(np.random.PCG64(m_half * 7 + n + k + epi))
     x = rng.standard_normal((2 * m_half, k))
     xd = act_to_dev(x, dtype)
