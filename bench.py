@@ -248,11 +248,16 @@ def main():
     roof["kernel"] = dom
     roof["avg_launch_ms"] = dom_ms / max(dom_n, 1)
     roof["work_per_launch"] = dom_work / max(dom_n, 1)
+    # HBM-side bytes per launch of the dominant kernel as rocprofv3's FETCH_SIZE + WRITE_SIZE counted them (a
+    # committed summary under profiles/, made with this same command); null for workloads that were not profiled
     roof["traffic"] = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not (args.batch or args.seq):
         try:
-            roof["traffic"] = json.load(open(tpath)).get(args.config, {}).get(dom)
+            detail = json.load(open(tpath)).get(args.config, {}).get(dom)
+            if detail:
+                roof["traffic"] = detail["fetch_bytes_per_launch"] + detail["write_bytes_per_launch"]
+                roof["traffic_detail"] = detail
         except Exception:
             roof["traffic"] = None
 
