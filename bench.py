@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--host-blocks", type=int, default=6,
                     help="streamed configs: number of distinct real-shape pinned host blocks; the layers cycle through them "
                          "(the full 175B model needs 348 GB of pinned memory, more than a box may pin)")
+    ap.add_argument("--writeback-interval", type=int, default=1,
+                    help="streamed configuration: write the updated blocks back to the host every K-th step (1 = every step, "
+                         "the paper's schedule)")
     ap.add_argument("--stochastic-update", action="store_true",
                     help="round the update of Eq. 2 stochastically into the 16-bit storage type (opt-in variant)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -198,6 +201,8 @@ def main():
     h = zo_amd.zo_init_model(cfg, tensors, ws, nbytes, c["batch"], c["seq"], stream, copy_stream)
     if args.stochastic_update:
         zo_amd.zo_set_update_rounding(h, zo_amd.ZO_ROUND_STOCHASTIC)
+    if streamed and args.writeback_interval != 1:
+        zo_amd.zo_set_writeback_interval(h, args.writeback_interval)
 
     def step(i):
         zo_amd.zo_step(h, tokens, c["batch"], c["seq"], i, c["eps"], c["lr"], zo_amd.ZO_MODE_FUSED, want_host=False)
@@ -282,7 +287,9 @@ def main():
         step_s = dt / args.steps
         out["streaming"] = {"block_bytes": block_bytes, "blocks_per_step": c["n_layers"], "distinct_host_blocks": int(host_ring.shape[0]),
                             "h2d_gbs": block_bytes * c["n_layers"] / step_s / 1e9,
-                            "d2h_gbs": block_bytes * c["n_layers"] / step_s / 1e9 if args.warmup + args.steps > 1 else 0.0,
+                            "d2h_gbs": (block_bytes * c["n_layers"] / step_s / 1e9 / args.writeback_interval
+                                        if args.warmup + args.steps > 1 else 0.0),
+                            "writeback_interval": args.writeback_interval,
                             "compute_ms_per_block": sum(v["ms_per_step"] for v in kernels.values()) / c["n_layers"],
                             "note": "layers cycle through the distinct host blocks, so values are not those of one model; "
                                     "traffic, kernels and schedule are those of the full model"}

@@ -145,9 +145,18 @@ int zo_stream_block(zo_model *m, int block, int phase_flags);
 int zo_stream_begin(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t seed, float eps);
 int zo_stream_end(zo_model *m, float lr, double *host_g, double *host_loss_pm);
 
-/* Apply the update left pending by the last streamed step to every tensor (as printed,
- * Alg. 2 never applies the last one).  No-op when nothing is pending. */
+/* Apply the updates that the host copies of a streamed model still lack (as printed, Alg. 2 never
+ * applies the last one) and write every block back.  No-op when nothing is pending. */
 int zo_flush_pending(zo_model *m);
+
+/* Streamed models: how often the updated blocks go back to pinned host memory.  1 (the default) is Alg. 3 as
+ * printed: every block is written back in every step, so the host link carries each block both ways.  With
+ * `steps` = K > 1 the host copies are left up to K steps behind: a block takes all the updates it lacks, in
+ * order, right after each upload (theta and the losses are bit for bit those of K = 1), and is written back
+ * only in every K-th step, which takes the download traffic off the link in the others.  zo_flush_pending
+ * brings the host copies up to date at any time.  1 <= steps <= 16.  ZO_ESTATE on a resident model or while
+ * updates are pending (flush first). */
+int zo_set_writeback_interval(zo_model *m, int steps);
 
 /* How the update of Eq. 2 is rounded into a 16-bit storage type.  ZO_ROUND_NEAREST (the default, and the
  * only rounding of every perturbation) is round-to-nearest-even.  ZO_ROUND_STOCHASTIC is an opt-in

@@ -21,7 +21,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 
 EXPORTS = (
     "zo_workspace_bytes", "zo_init_model", "zo_perturb", "zo_dual_forward", "zo_step", "zo_stream_block",
-    "zo_stream_begin", "zo_stream_end", "zo_flush_pending", "zo_set_update_rounding", "zo_device_flags", "zo_free",
+    "zo_stream_begin", "zo_stream_end", "zo_flush_pending", "zo_set_writeback_interval", "zo_set_update_rounding", "zo_device_flags", "zo_free",
     "zo_last_error", "zo_profile_begin", "zo_profile_end",
     "zo_kernel_z", "zo_kernel_normal_pairs", "zo_kernel_axpy_z", "zo_kernel_axpy_z_sr", "zo_kernel_stage_pm", "zo_kernel_linear_pm",
     "zo_kernel_layernorm_pm", "zo_kernel_attention", "zo_kernel_lmhead_scratch_bytes", "zo_kernel_lmhead_ce",
@@ -66,6 +66,7 @@ def lib():
         L.zo_stream_end.argtypes = [vp, f32, vp, vp]
         L.zo_flush_pending.argtypes = [vp]
         L.zo_set_update_rounding.argtypes = [vp, i32]
+        L.zo_set_writeback_interval.argtypes = [vp, i32]
         L.zo_device_flags.argtypes = [vp, ctypes.POINTER(u32)]
         L.zo_free.argtypes = [vp]
         L.zo_profile_begin.argtypes = [vp, i32]
@@ -168,6 +169,10 @@ def zo_stream_end(model, lr, want_host=True):
 
 def zo_flush_pending(model):
     _check(lib().zo_flush_pending(model))
+
+
+def zo_set_writeback_interval(model, steps):
+    _check(lib().zo_set_writeback_interval(model, steps))
 
 
 def zo_set_update_rounding(model, mode):

@@ -144,6 +144,8 @@ Workspace plan_workspace(const zo_config &c, int batch, int seq)
 
 }  // namespace
 
+constexpr int kMaxPending = kMaxUpdates;   // longest write-back interval of a streamed model
+
 struct zo_model {
     zo_config cfg;
     int n_tensors, max_batch, max_seq;
@@ -158,15 +160,20 @@ struct zo_model {
     bool use_mfma;
     // device scalars
     double *loss_pm, *g;
-    float *s_cur, *s_pending;
+    float *s_cur, *s_pend;             // update scalars on the device: this step's (resident model), the pending steps' (streamed)
     uint32_t *flags;
     // streamed state
     hipEvent_t ev_uploaded[2], ev_staged[2], ev_written[2];
     int slot_block[2];
     SlotState slot_state[2];
     bool slot_dirty[2];
-    bool pending;
-    uint64_t pending_seed;
+    // Streamed model: the steps whose update the host copies of the blocks do not hold yet, oldest first.  Each
+    // block takes them, in order, right after its next upload; the blocks are written back in the step that finds
+    // wb_interval of them (1 = Alg. 3 as printed: every step), after which the list starts again.  The tensors that
+    // stay in HBM only ever lack the newest one.
+    int wb_interval, pend_n;
+    uint64_t pend_seed[kMaxPending];
+    bool resident_pending;
     int update_rounding;               // ZO_ROUND_*: how the update of Eq. 2 goes into a 16-bit type
     bool step_open;
     int next_block;
@@ -452,16 +459,30 @@ int stream_prefetch(zo_model *m, int block)
 }
 
 // wait for the upload, apply the pending update, optionally stage + forward
-int stream_compute(zo_model *m, int block, bool forward)
+int stream_compute(zo_model *m, int block, bool forward, bool force_writeback = false)
 {
     const int slot = block & 1;
     if (m->slot_state[slot] != SLOT_UPLOADED || m->slot_block[slot] != block)
         return fail(ZO_ESTATE, "block %d was not prefetched", block);
     ZO_HIP(hipStreamWaitEvent(m->compute, m->ev_uploaded[slot], 0));
-    if (m->pending) {
-        ZO_TRY(axpy_range(m, 2 + kPerBlock * block, kPerBlock, m->pending_seed, 0.0f, m->s_pending, true));
-        m->slot_dirty[slot] = true;
+    if (m->pend_n == 1) {
+        ZO_TRY(axpy_range(m, 2 + kPerBlock * block, kPerBlock, m->pend_seed[0], 0.0f, m->s_pend, true));
+    } else if (m->pend_n > 1) {      // all of them in one pass over the block
+        const int first = 2 + kPerBlock * block;
+        UpdateSeeds upd{};
+        upd.n = m->pend_n;
+        double bytes = 0;
+        for (int j = 0; j < m->pend_n; ++j) upd.seed[j] = m->pend_seed[j];
+        for (int t = first; t < first + kPerBlock; ++t) bytes += 2.0 * (double)m->descs[t].numel * elem_bytes(m->cfg.dtype);
+        const uint64_t c0 = m->descs[first].first_chunk;
+        const uint64_t c1 = first + kPerBlock < m->n_tensors ? m->descs[first + kPerBlock].first_chunk : m->total_chunks;
+        ZO_PROF(m, K_UPDATE, bytes * m->pend_n,
+                launch_axpy_updates(wsp_ptr<TensorDesc>(m, m->wsp.descs) + first, kPerBlock, c0, c1 - c0, m->cfg.dtype, upd, m->s_pend,
+                                    m->update_rounding == ZO_ROUND_STOCHASTIC, m->compute));
     }
+    // the updated copy goes back to the host only in the step that closes a write-back interval (or at a flush);
+    // otherwise it is dropped after use and the host copy stays pend_n steps behind
+    m->slot_dirty[slot] = m->pend_n > 0 && (m->pend_n >= m->wb_interval || force_writeback);
     if (forward) ZO_TRY(stage_block(m, block, m->ws + m->wsp.slot[slot], m->step_seed, m->step_eps, false));
     ZO_HIP(hipEventRecord(m->ev_staged[slot], m->compute));
     if (forward) ZO_TRY(block_forward(m, 2, m->step_batch, m->step_seq));
@@ -490,9 +511,10 @@ int stream_begin(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_
     const zo_config &c = m->cfg;
     const int lnf = 2 + kPerBlock * c.n_layers;
     m->step_seed = seed; m->step_eps = eps; m->step_batch = batch; m->step_seq = seq;
-    if (m->pending) {   // Alg. 2: the resident modules take last step's update at their visit
-        ZO_TRY(axpy_range(m, 0, 2, m->pending_seed, 0.0f, m->s_pending, true));
-        ZO_TRY(axpy_range(m, lnf, 2, m->pending_seed, 0.0f, m->s_pending, true));
+    if (m->resident_pending) {   // Alg. 2: the resident modules take last step's update at their visit
+        ZO_TRY(axpy_range(m, 0, 2, m->pend_seed[m->pend_n - 1], 0.0f, m->s_pend + (m->pend_n - 1), true));
+        ZO_TRY(axpy_range(m, lnf, 2, m->pend_seed[m->pend_n - 1], 0.0f, m->s_pend + (m->pend_n - 1), true));
+        m->resident_pending = false;
     }
     ZO_TRY(stage_globals(m, seq, seed, eps));
     ZO_TRY(embed(m, tokens, 2, batch, seq, m->ws + m->wsp.e_pm[0], m->ws + m->wsp.e_pm[1], m->ws + m->wsp.pos_pm[0],
@@ -508,9 +530,10 @@ int stream_end(zo_model *m, float lr)
     if (m->next_block != m->cfg.n_layers) return fail(ZO_ESTATE, "only %d of %d blocks were computed", m->next_block, m->cfg.n_layers);
     ZO_TRY(head_and_loss(m, 2, m->step_batch, m->step_seq, m->ws + m->wsp.e_pm[0], m->ws + m->wsp.e_pm[1], m->ws + m->wsp.lnf_pm[0],
                          m->ws + m->wsp.lnf_pm[1], m->loss_pm));
-    ZO_HIP(launch_g_scalar(m->loss_pm, m->step_eps, lr, m->g, m->s_pending, m->flags, m->compute));
-    m->pending = true;
-    m->pending_seed = m->step_seed;
+    if (m->pend_n >= m->wb_interval) m->pend_n = 0;       // this step's uploads took them all and were written back
+    ZO_HIP(launch_g_scalar(m->loss_pm, m->step_eps, lr, m->g, m->s_pend + m->pend_n, m->flags, m->compute));
+    m->pend_seed[m->pend_n++] = m->step_seed;
+    m->resident_pending = true;
     m->step_open = false;
     return ZO_OK;
 }
@@ -574,12 +597,13 @@ extern "C" int zo_init_model(const zo_config *cfg, void *const *tensor_ptrs, int
     }
     m->total_chunks = chunk;
     char *sc = m->ws + wsp.scalars;
-    m->loss_pm = (double *)sc; m->g = (double *)(sc + 16); m->s_cur = (float *)(sc + 24); m->s_pending = (float *)(sc + 28);
+    m->loss_pm = (double *)sc; m->g = (double *)(sc + 16); m->s_cur = (float *)(sc + 24);
     m->flags = (uint32_t *)(sc + 32);
+    m->s_pend = (float *)(sc + 64);                     // kMaxPending floats
     hipError_t err = hipMemcpy(m->ws + wsp.descs, m->descs.data(), sizeof(TensorDesc) * n_tensors, hipMemcpyHostToDevice);
     if (err == hipSuccess) err = hipMemset(sc, 0, 256);
     if (err != hipSuccess) { delete m; return fail(ZO_EHIP, "initialising the workspace failed: %s", hipGetErrorString(err)); }
-    m->pending = false; m->step_open = false; m->next_block = 0; m->prof_on = false; m->prof_n = 0;
+    m->wb_interval = 1; m->pend_n = 0; m->resident_pending = false; m->step_open = false; m->next_block = 0; m->prof_on = false; m->prof_n = 0;
     for (int s = 0; s < 2; ++s) {
         m->slot_block[s] = -1; m->slot_state[s] = SLOT_EMPTY; m->slot_dirty[s] = false;
         m->ev_uploaded[s] = m->ev_staged[s] = m->ev_written[s] = nullptr;
@@ -723,23 +747,36 @@ extern "C" int zo_set_update_rounding(zo_model *m, int mode)
     return ZO_OK;
 }
 
+extern "C" int zo_set_writeback_interval(zo_model *m, int steps)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    if (m->cfg.residency != ZO_STREAMED) return fail(ZO_ESTATE, "not a streamed model");
+    if (steps < 1 || steps > kMaxPending) return fail(ZO_EINVAL, "write-back interval %d outside 1 .. %d", steps, kMaxPending);
+    if (m->step_open || m->pend_n != 0) return fail(ZO_ESTATE, "updates are pending: call zo_flush_pending first");
+    m->wb_interval = steps;
+    return ZO_OK;
+}
+
 extern "C" int zo_flush_pending(zo_model *m)
 {
     if (!m) return fail(ZO_EINVAL, "model is NULL");
-    if (m->cfg.residency != ZO_STREAMED || !m->pending) return ZO_OK;
+    if (m->cfg.residency != ZO_STREAMED || m->pend_n == 0) return ZO_OK;
     if (m->step_open) return fail(ZO_ESTATE, "a streamed step is open");
     const int lnf = 2 + kPerBlock * m->cfg.n_layers;
-    ZO_TRY(axpy_range(m, 0, 2, m->pending_seed, 0.0f, m->s_pending, true));
-    ZO_TRY(axpy_range(m, lnf, 2, m->pending_seed, 0.0f, m->s_pending, true));
+    if (m->resident_pending) {
+        ZO_TRY(axpy_range(m, 0, 2, m->pend_seed[m->pend_n - 1], 0.0f, m->s_pend + (m->pend_n - 1), true));
+        ZO_TRY(axpy_range(m, lnf, 2, m->pend_seed[m->pend_n - 1], 0.0f, m->s_pend + (m->pend_n - 1), true));
+        m->resident_pending = false;
+    }
     ZO_TRY(stream_prefetch(m, 0));
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         if (l + 1 < m->cfg.n_layers) ZO_TRY(stream_prefetch(m, l + 1));
-        ZO_TRY(stream_compute(m, l, false));
+        ZO_TRY(stream_compute(m, l, false, true));
         ZO_TRY(stream_writeback(m, l));
     }
     ZO_HIP(hipStreamSynchronize(m->download));
     ZO_HIP(hipStreamSynchronize(m->compute));
-    m->pending = false;
+    m->pend_n = 0;
     return ZO_OK;
 }
 

@@ -37,6 +37,11 @@ hipError_t launch_normal_pairs(const uint32_t *words, float *z, uint64_t n_pairs
 // descs in device memory: n_desc consecutive entries whose chunks are chunk_offset .. chunk_offset + total_chunks - 1
 hipError_t launch_axpy_multi(const TensorDesc *dev_descs, int n_desc, uint64_t chunk_offset, uint64_t total_chunks,
                              int dtype, uint64_t seed, float scale, const float *dev_scale, bool stochastic, hipStream_t s);
+// the same over several updates in one pass: theta <- rn(fma(dev_scales[j], z(seeds[j]), theta)), j = 0 .. n-1 in order
+constexpr int kMaxUpdates = 16;
+struct UpdateSeeds { int n; uint64_t seed[kMaxUpdates]; };
+hipError_t launch_axpy_updates(const TensorDesc *dev_descs, int n_desc, uint64_t chunk_offset, uint64_t total_chunks, int dtype,
+                               const UpdateSeeds &upd, const float *dev_scales, bool stochastic, hipStream_t s);
 hipError_t launch_axpy_single(const TensorDesc &d, int dtype, uint64_t seed, float scale,
                               const float *dev_scale, bool stochastic, hipStream_t s);
 // both signs (eps) or a plain (transposing) copy when single_copy

@@ -142,6 +142,68 @@ __global__ __launch_bounds__(256) void axpy_z_kernel(const TensorDesc *__restric
     }
 }
 
+// Several updates of Eq. 2 in one pass (a streamed block that is several steps behind takes them all right
+// after its upload): theta <- rn(fma(s_j, z_j, theta)) for j = 0 .. n-1 in this order, each rounded into the
+// storage type before the next starts from it, exactly as n separate passes would leave it, with one read and
+// one write of theta.  Same chunking and addressing as axpy_z_kernel; the scalars are dev_scale[0 .. n-1].
+template <int DT, bool SR>
+__global__ __launch_bounds__(256) void axpy_z_multi_kernel(const TensorDesc *__restrict__ descs, int n_desc, uint64_t chunk_offset,
+                                                           UpdateSeeds upd, const float *__restrict__ dev_scale)
+{
+    using W = typename Prec<DT>::W;
+    constexpr int VN = Vec16<DT>::N;
+    const uint64_t chunk = (uint64_t)blockIdx.x + chunk_offset;
+    int lo = 0, hi = n_desc - 1;                      // last descriptor whose first_chunk <= chunk
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (descs[mid].first_chunk <= chunk) lo = mid; else hi = mid - 1;
+    }
+    const TensorDesc d = descs[lo];
+    const uint64_t base = (chunk - d.first_chunk) * kAxpyChunk;
+    const W *__restrict__ src = (const W *)d.src;
+    W *__restrict__ dst = (W *)d.dst;
+    constexpr int kIter = kAxpyChunk / (256 * VN);
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+        const uint64_t i0 = base + (uint64_t)(it * 256 + threadIdx.x) * VN;
+        if (i0 >= d.numel) break;
+        const bool whole = i0 + VN <= d.numel;
+        float th[VN];
+        if (whole) {
+            unpack16<DT>(*(const uint4 *)(src + i0), th);
+        } else {
+            for (int e = 0; e < VN; ++e) th[e] = i0 + e < d.numel ? Prec<DT>::w2f(src[i0 + e]) : 0.0f;
+        }
+        uint4 packed = uint4{0u, 0u, 0u, 0u};
+        for (int j = 0; j < upd.n; ++j) {
+            const uint64_t seed = upd.seed[j];
+            const float sc = dev_scale[j];
+            float z[VN];
+#pragma unroll
+            for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b);
+#pragma unroll
+            for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
+            if constexpr (SR) {
+                uint32_t rw[VN];
+#pragma unroll
+                for (int b = 0; b < VN / 4; ++b) {
+                    const u32x4 r = philox_block(seed, d.tid, i0 / 4 + b, 3u);
+                    rw[4 * b] = r.x; rw[4 * b + 1] = r.y; rw[4 * b + 2] = r.z; rw[4 * b + 3] = r.w;
+                }
+                packed = pack16_sr<DT>(th, rw);
+            } else {
+                packed = pack16<DT>(th);
+            }
+            unpack16<DT>(packed, th);                 // the next update starts from the stored value
+        }
+        if (whole) {
+            *(uint4 *)(dst + i0) = packed;
+        } else {
+            for (int e = 0; e < VN && i0 + e < d.numel; ++e) dst[i0 + e] = Prec<DT>::f2w(th[e]);   // exact: th holds stored values
+        }
+    }
+}
+
 // ------------------------------------------------------------------ staging W+ / W-
 // Flat tiles copy kStageFlatTile consecutive elements; transposing tiles move a 64 x 64 patch
 // of a [rows, cols] matrix through LDS so that both the read (along cols) and the write
@@ -325,6 +387,35 @@ hipError_t launch_axpy_multi(const TensorDesc *dev_descs, int n_desc, uint64_t c
     case kFP32: return axpy_launch_t<kFP32>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, stochastic, s);
     case kBF16: return axpy_launch_t<kBF16>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, stochastic, s);
     case kFP16: return axpy_launch_t<kFP16>(dev_descs, n_desc, none, chunk_offset, total_chunks, seed, scale, dev_scale, stochastic, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <int DT>
+static hipError_t axpy_multi_launch_t(const TensorDesc *descs, int n_desc, uint64_t chunk_offset, uint64_t chunks,
+                                      const UpdateSeeds &upd, const float *dev_scales, bool stochastic, hipStream_t s)
+{
+    if (chunks == 0 || upd.n == 0) return hipSuccess;
+    if (chunks > 0x7fffffffull || upd.n < 0 || upd.n > kMaxUpdates || !descs || !dev_scales) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)chunks), block(256);
+    if constexpr (DT != kFP32) {
+        if (stochastic) {
+            axpy_z_multi_kernel<DT, true><<<grid, block, 0, s>>>(descs, n_desc, chunk_offset, upd, dev_scales);
+            return hipGetLastError();
+        }
+    }
+    if (stochastic) return hipErrorInvalidValue;
+    axpy_z_multi_kernel<DT, false><<<grid, block, 0, s>>>(descs, n_desc, chunk_offset, upd, dev_scales);
+    return hipGetLastError();
+}
+
+hipError_t launch_axpy_updates(const TensorDesc *dev_descs, int n_desc, uint64_t chunk_offset, uint64_t total_chunks, int dtype,
+                               const UpdateSeeds &upd, const float *dev_scales, bool stochastic, hipStream_t s)
+{
+    switch (dtype) {
+    case kFP32: return axpy_multi_launch_t<kFP32>(dev_descs, n_desc, chunk_offset, total_chunks, upd, dev_scales, stochastic, s);
+    case kBF16: return axpy_multi_launch_t<kBF16>(dev_descs, n_desc, chunk_offset, total_chunks, upd, dev_scales, stochastic, s);
+    case kFP16: return axpy_multi_launch_t<kFP16>(dev_descs, n_desc, chunk_offset, total_chunks, upd, dev_scales, stochastic, s);
     }
     return hipErrorInvalidValue;
 }

@@ -102,3 +102,45 @@ def test_manual_schedule_equals_zo_step_and_state_errors():
     lp, lm, g = zo_amd.zo_stream_end(b.handle, 1e-3)
     assert np.isfinite(g)
     a.close(); b.close()
+
+
+@pytest.mark.parametrize("dtype,interval", [(zi.BF16, 3), (zi.FP16, 2), (zi.FP32, 4)])
+def test_writeback_interval_leaves_results_bit_identical(dtype, interval):
+    """Blocks written back only every `interval` steps: losses, g and (after a flush) theta are bit for bit those
+    of the resident model; between write-backs the host copies lag; the setting can only change with nothing
+    pending."""
+    lr = {zi.BF16: 3e-2, zi.FP16: 3e-3, zi.FP32: 1e-3}[dtype]
+    res, stm = _pair(dtype)
+    zo_amd.zo_set_writeback_interval(stm.handle, interval)
+    if dtype == zi.FP16:            # the one-pass multi-update kernel with the stochastic rounding as well
+        for mdl in (res, stm):
+            zo_amd.zo_set_update_rounding(mdl.handle, zo_amd.ZO_ROUND_STOCHASTIC)
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_set_writeback_interval(res.handle, 2)            # not a streamed model
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_set_writeback_interval(stm.handle, 17)
+    tok, tok_dev = res.tokens()
+    block_ids = range(2, 2 + 16 * SHAPE["n_layers"])
+    stale_seen = False
+    for seed in range(2 * interval + 2):
+        a = zo_amd.zo_step(res.handle, tok_dev, 2, 40, seed, 1e-3, lr)
+        b = zo_amd.zo_step(stm.handle, tok_dev, 2, 40, seed, 1e-3, lr)
+        assert a == b, (seed, a, b)
+        host = stm.theta()
+        if seed == 0:
+            assert all(host[i].tobytes() == stm.theta0[i].tobytes() for i in block_ids)     # nothing written back yet
+        if seed == interval:        # the step that found `interval` pending updates wrote the blocks back
+            assert any(host[i].tobytes() != stm.theta0[i].tobytes() for i in block_ids)
+            stale_seen = True
+    assert stale_seen
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_set_writeback_interval(stm.handle, 1)            # updates pending
+    zo_amd.zo_flush_pending(stm.handle)
+    assert all(x.tobytes() == y.tobytes() for x, y in zip(res.theta(), stm.theta()))
+    zo_amd.zo_set_writeback_interval(stm.handle, 1)                # allowed again after the flush
+    a = zo_amd.zo_step(res.handle, tok_dev, 2, 40, 99, 1e-3, lr)
+    b = zo_amd.zo_step(stm.handle, tok_dev, 2, 40, 99, 1e-3, lr)
+    assert a == b
+    zo_amd.zo_flush_pending(stm.handle)
+    assert all(x.tobytes() == y.tobytes() for x, y in zip(res.theta(), stm.theta()))
+    res.close(); stm.close()
