@@ -129,11 +129,12 @@ int zo_step(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t see
 /* Alg. 3's three operations on one block of a ZO_STREAMED model, for callers that drive
  * the schedule themselves (zo_step does this internally):
  *   PREFETCH   U(W_block): enqueue the host->device copy into slot block % 2 on the copy stream.
- *   COMPUTE    C(W_block): on the compute stream, wait for the upload, apply the pending update
- *              (if any), then the dual forward of this block on the activations left by the
- *              previous COMPUTE.  Blocks must be computed in order 0,1,..,L-1 after
+ *   COMPUTE    C(W_block): on the compute stream, wait for the upload, apply the updates the host
+ *              copy lacks (if any), then the dual forward of this block on the activations left by
+ *              the previous COMPUTE.  Blocks must be computed in order 0,1,..,L-1 after
  *              zo_stream_begin.
- *   WRITEBACK  O(W_block): wait for COMPUTE, copy the (updated) block back to its pinned-host home.
+ *   WRITEBACK  O(W_block): wait for COMPUTE, copy the updated block back to its pinned-host home
+ *              (nothing to do in a step that does not close a write-back interval).
  * Flags may be OR-ed; they are issued in the order PREFETCH, COMPUTE, WRITEBACK.
  * ZO_ESTATE: not a streamed model, no step open, COMPUTE of a block that was not prefetched or
  * out of order, PREFETCH into a slot whose occupant still awaits COMPUTE. */

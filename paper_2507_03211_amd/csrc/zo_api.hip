@@ -458,7 +458,7 @@ int stream_prefetch(zo_model *m, int block)
     return ZO_OK;
 }
 
-// wait for the upload, apply the pending update, optionally stage + forward
+// wait for the upload, apply the updates the host copy lacks, optionally stage + forward
 int stream_compute(zo_model *m, int block, bool forward, bool force_writeback = false)
 {
     const int slot = block & 1;
