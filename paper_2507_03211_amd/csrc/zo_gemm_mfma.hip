@@ -308,39 +308,42 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     };
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
     const int nk = k / BK;                              // >= 3 (the launcher sees to it)
-    // Slabs are numbered through all the tiles of this workgroup (slab g of tile number it, k-slab kt: g = it nk + kt).
-    // x slab g lives in x stage g % 3, w slab g in w stage g % 2 (after the three x stages).
-    auto x_stage = [&](int g) { return lds_base + (uint32_t)(g % STX) * (kTileU4 * 16) + (uint32_t)wave * 8192u; };
-    auto w_stage = [&](int g) { return lds_base + (uint32_t)(STX + g % STW) * (kTileU4 * 16) + (uint32_t)wave * 8192u; };
+    // Slabs are numbered through all the tiles of this workgroup.  x slab g lives in x stage g % 3, w slab g in w
+    // stage g % 2 (after the three x stages); the stages of slabs g, g+1, g+2 are kept as rotating scalars (uint4
+    // index into smem) instead of being worked out from g every time.
+    constexpr uint32_t kStage = kTileU4;                 // uint4 per stage
+    uint32_t xs0 = 0, xs1 = kStage, xs2 = 2 * kStage;    // x stages of slabs g, g+1, g+2
+    uint32_t ws0 = STX * kStage, ws1 = (STX + 1) * kStage;   // w stages of slabs g (and g+2), g+1
+    auto lds_of = [&](uint32_t stage) { return lds_base + stage * 16u + (uint32_t)wave * 8192u; };   // this wave's slice
 
     f32x16 acc[4][4];
     const int fr = lane & 31, fh = lane >> 5, sw = (fr >> 1) & 7;
     const int xrow = (wm * 128 + fr) * 8, wrow = (wn * 128 + fr) * 8;     // uint4 index of the lane's first rows
     uint4 wfa[4], xfa[4], wfb[4], xfb[4];                                 // two fragment sets: one multiplies while one loads
-    // One fragment of set (wf, xf) for k-step ks of slab g, in the order the multiplies need them:
+    // One fragment of set (wf, xf) for k-step ks of the slab in stages (xst, wst), in the order the multiplies need them:
     // wf0, xf0, xf1, xf2, xf3, wf1, wf2, wf3.
-    auto frag1 = [&](int g, int ks, int idx, uint4 (&wf)[4], uint4 (&xf)[4]) {
-        const uint4 *xs = smem + (g % STX) * kTileU4;
-        const uint4 *ws = smem + (STX + g % STW) * kTileU4;
+    auto frag1 = [&](uint32_t xst, uint32_t wst, int ks, int idx, uint4 (&wf)[4], uint4 (&xf)[4]) {
+        const uint4 *xs = smem + xst;
+        const uint4 *ws = smem + wst;
         const int slot = (2 * ks + fh) ^ sw;
         if (idx == 0) wf[0] = ws[wrow + slot];
         else if (idx <= 4) xf[idx - 1] = xs[xrow + (idx - 1) * 256 + slot];
         else wf[idx - 4] = ws[wrow + (idx - 4) * 256 + slot];
     };
     // Multiplies j0 .. j1-1 of the 4 x 4 fragment product of set (wf, xf).  Before multiply j:
-    //  * fragments rper (j - rj0) / revery .. + rper - 1 of set (nwf, nxf) are read for k-step nks of slab ng,
-    //    when that divides;
+    //  * fragments rper (j - rj0) / revery .. + rper - 1 of set (nwf, nxf) are read for k-step nks of the slab in
+    //    stages (nxst, nwst), when that divides;
     //  * load lfirst + (j - lj0) / levery (lane offsets `offs` from the scalar base `gbase`) goes out into LDS at
     //    `st`, when that divides, `nload` in all.
     //  `first`: the product starts the accumulators (first quarter of a tile's first slab) instead of adding to them.
-    auto mma_rl = [&](const uint4 (&wf)[4], const uint4 (&xf)[4], int j0, int j1, uint4 (&nwf)[4], uint4 (&nxf)[4], int ng,
-                      int nks, int rj0, int revery, int rper, const uint32_t (&offs)[8], uint64_t gbase, uint32_t st,
+    auto mma_rl = [&](const uint4 (&wf)[4], const uint4 (&xf)[4], int j0, int j1, uint4 (&nwf)[4], uint4 (&nxf)[4], uint32_t nxst,
+                      uint32_t nwst, int nks, int rj0, int revery, int rper, const uint32_t (&offs)[8], uint64_t gbase, uint32_t st,
                       int lfirst, int nload, int lj0, int levery, bool first = false) {
 #pragma unroll
         for (int j = j0; j < j1; ++j) {
             if (j >= rj0 && (j - rj0) % revery == 0 && (j - rj0) / revery * rper < 8) {
 #pragma unroll
-                for (int r = 0; r < rper; ++r) frag1(ng, nks, (j - rj0) / revery * rper + r, nwf, nxf);
+                for (int r = 0; r < rper; ++r) frag1(nxst, nwst, nks, (j - rj0) / revery * rper + r, nwf, nxf);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (j >= lj0 && (j - lj0) % levery == 0 && (j - lj0) / levery < nload) {
@@ -373,38 +376,42 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
     // the lane offsets (xo, wo).  x(g+2) goes into the activation stage that slab g-1 left at the previous barrier:
     // its 8 loads sit under the 40 multiplies before this slab's barrier; w(g+2) can only follow the barrier: its
     // 8 loads sit under the 24 multiplies after it.
-    auto slab = [&](int g, uint64_t xb, uint64_t wb, const uint32_t (&xo)[8], const uint32_t (&wo)[8], bool first) {
-        const uint32_t stx = x_stage(g + 2), stw = w_stage(g + 2);
-        mma_rl(wfa, xfa, 0, 16, wfb, xfb, g, 1, 1, 2, 1, xo, xb, stx, 0, 3, 0, 6, first);
-        mma_rl(wfb, xfb, 0, 16, wfa, xfa, g, 2, 1, 2, 1, xo, xb, stx, 3, 3, 0, 6);
+    auto slab = [&](uint64_t xb, uint64_t wb, const uint32_t (&xo)[8], const uint32_t (&wo)[8], bool first) {
+        const uint32_t stx = lds_of(xs2), stw = lds_of(ws0);
+        mma_rl(wfa, xfa, 0, 16, wfb, xfb, xs0, ws0, 1, 1, 2, 1, xo, xb, stx, 0, 3, 0, 6, first);
+        mma_rl(wfb, xfb, 0, 16, wfa, xfa, xs0, ws0, 2, 1, 2, 1, xo, xb, stx, 3, 3, 0, 6);
         // the last fragments of slab g, two reads at a time, so that they have landed when the barrier's wait comes
-        mma_rl(wfa, xfa, 0, 8, wfb, xfb, g, 3, 0, 1, 2, xo, xb, stx, 6, 2, 4, 2);
+        mma_rl(wfa, xfa, 0, 8, wfb, xfb, xs0, ws0, 3, 0, 1, 2, xo, xb, stx, 6, 2, 4, 2);
         // slab g+1 landed (only x(g+2), the 8 newest loads, may still be out); slab g fully in registers
         asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        mma_rl(wfa, xfa, 8, 16, wfb, xfb, g, 3, 99, 1, 1, wo, wb, stw, 0, 3, 8, 3);
+        mma_rl(wfa, xfa, 8, 16, wfb, xfb, xs0, ws0, 3, 99, 1, 1, wo, wb, stw, 0, 3, 8, 3);
         // the first fragments of slab g+1 early in the quarter: the loop's back edge waits for all LDS reads
-        mma_rl(wfb, xfb, 0, 16, wfa, xfa, g + 1, 0, 0, 1, 1, wo, wb, stw, 3, 5, 0, 3);
+        mma_rl(wfb, xfb, 0, 16, wfa, xfa, xs1, ws1, 0, 0, 1, 1, wo, wb, stw, 3, 5, 0, 3);
+        // on to the next slab: the stage this one leaves is the one that slab g+3 will be loaded into
+        const uint32_t tx = xs0, tw = ws0;
+        xs0 = xs1; xs1 = xs2; xs2 = tx;
+        ws0 = ws1; ws1 = tw;
     };
 
     Tile cur, nxt;
     int lin = tile_lin(0);
     if (lin < 0) return;
     setup(lin, cur);
-    int it = 0, g0 = 0;                                 // tile number of this workgroup, its first slab
+    int it = 0;                                         // tile number of this workgroup
     // prologue of the first tile only: slabs 0 and 1, fragments of the first quarter
 #pragma unroll
-    for (int i = 0; i < 8; ++i) gload_lds16(cur.xbase, cur.xg[i], x_stage(0) + i * 1024u);
+    for (int i = 0; i < 8; ++i) gload_lds16(cur.xbase, cur.xg[i], lds_of(xs0) + i * 1024u);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) gload_lds16(cur.wbase, cur.wg[i], w_stage(0) + i * 1024u);
+    for (int i = 0; i < 8; ++i) gload_lds16(cur.wbase, cur.wg[i], lds_of(ws0) + i * 1024u);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) gload_lds16(cur.xbase + 2u * BK, cur.xg[i], x_stage(1) + i * 1024u);
+    for (int i = 0; i < 8; ++i) gload_lds16(cur.xbase + 2u * BK, cur.xg[i], lds_of(xs1) + i * 1024u);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) gload_lds16(cur.wbase + 2u * BK, cur.wg[i], w_stage(1) + i * 1024u);
+    for (int i = 0; i < 8; ++i) gload_lds16(cur.wbase + 2u * BK, cur.wg[i], lds_of(ws1) + i * 1024u);
     asm volatile("s_waitcnt vmcnt(16)" ::: "memory");               // slab 0 landed
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int idx = 0; idx < 8; ++idx) frag1(0, 0, idx, wfa, xfa);
+    for (int idx = 0; idx < 8; ++idx) frag1(xs0, ws0, 0, idx, wfa, xfa);
 
     for (;;) {
         const int lin_next = tile_lin(it + 1);
@@ -418,13 +425,12 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
             nxt.wbase += 2u * (uint32_t)((nk - 2) * BK);
         }
         // all slabs but the last two load two slabs ahead in this tile; the first one starts the accumulators
-        slab(g0, cur.xbase + 2u * (uint32_t)(2 * BK), cur.wbase + 2u * (uint32_t)(2 * BK), cur.xg, cur.wg, true);
+        slab(cur.xbase + 2u * (uint32_t)(2 * BK), cur.wbase + 2u * (uint32_t)(2 * BK), cur.xg, cur.wg, true);
         for (int kt = 1; kt < nk - 2; ++kt)
-            slab(g0 + kt, cur.xbase + 2u * (uint32_t)((kt + 2) * BK), cur.wbase + 2u * (uint32_t)((kt + 2) * BK), cur.xg, cur.wg, false);
+            slab(cur.xbase + 2u * (uint32_t)((kt + 2) * BK), cur.wbase + 2u * (uint32_t)((kt + 2) * BK), cur.xg, cur.wg, false);
         // the last two load the first two slabs of the next tile
-        slab(g0 + nk - 2, nxt.xbase, nxt.wbase, nxt.xg, nxt.wg, false);
-        slab(g0 + nk - 1, nxt.xbase + 2u * BK, nxt.wbase + 2u * BK, nxt.xg, nxt.wg, false);
-        const int g_last = g0 + nk - 1;
+        slab(nxt.xbase, nxt.wbase, nxt.xg, nxt.wg, false);
+        slab(nxt.xbase + 2u * BK, nxt.wbase + 2u * BK, nxt.xg, nxt.wg, false);
 
         // ---- epilogue of tile `cur`
         const int sign = cur.sign, m0 = cur.m0, n0 = cur.n0;
@@ -454,7 +460,7 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
             constexpr bool kOut16 = (EPI == 0 || EPI == 1);              // 2-byte outputs; else fp32
             constexpr int RP = kOut16 ? 32 : 16;                         // rows per pass
             constexpr int NPASS = 128 / RP;
-            char *stage = (char *)smem + (size_t)(g_last % STX) * (kTileU4 * 16) + wave * 8192;
+            char *stage = (char *)(smem + xs2) + wave * 8192;        // xs2: the stage the tile's last slab has just left
             const int ncol0 = n0 + wn * 128;
             // Bias: 2-byte outputs take it before the rounding, so per run of the MFMA layout (the same 16 runs
             // for every row block); fp32 outputs take it after the LDS pass, where a lane always holds the same
@@ -569,7 +575,6 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
         }
         if (!has_next) break;
         cur = nxt;
-        g0 += nk;
         ++it;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // the tail loads land before LDS is released
