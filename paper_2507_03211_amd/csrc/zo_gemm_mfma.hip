@@ -12,14 +12,15 @@
 // one output row, which makes the epilogue 8/16-byte stores.
 //
 // Two tilings:
-//  * 256 x 256 x 64, 4 waves of 128 x 128 (4 x 4 MFMA tiles, 256 accumulator registers), one
-//    workgroup per CU.  Operand tiles go from global memory straight into LDS
-//    (global_load_lds_dwordx4, no register staging), whole 128-byte lines per tile row; the 160 KiB
-//    of LDS hold three stages of the activation tile and two of the weight tile.  16-byte chunks are XOR-swizzled
-//    on the global side so that fragment reads are free of bank conflicts.  Workgroups are renumbered so that
-//    each XCD (its own L2) owns a contiguous band of 8 tile-rows and walks it column by column.
-//  * 128 x 128 x 64, 4 waves of 64 x 64, register-staged double buffer: for shapes with too few
-//    256-tiles to fill 256 CUs and for ragged small cases.
+//  * 256 x 256 x 64, 4 waves of 128 x 128 (4 x 4 MFMA tiles, 256 accumulator registers), one persistent
+//    workgroup per CU that walks its XCD's share of the tile list.  Operand tiles go from global memory
+//    straight into LDS (global_load_lds_dwordx4, no register staging), whole 128-byte lines per tile row; the
+//    160 KiB of LDS hold three stages of the activation tile and two of the weight tile, and the pipeline
+//    runs on from one tile into the next.  16-byte chunks are XOR-swizzled on the global side so that
+//    fragment reads are free of bank conflicts.  Tiles are numbered so that each XCD (its own L2) owns a
+//    contiguous band of 8 tile-rows and walks it column by column.  Outputs leave through LDS as whole rows.
+//  * 128 x 128 x 64, 4 waves of 64 x 64, register-staged double buffer: for shapes with fewer than 128
+//    256-tiles, K below three slabs, and ragged small cases.
 #include "zo_kernels.h"
 #include "zo_types.hip.h"
 
@@ -227,7 +228,7 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__rest
     }
 }
 
-// ------------------------------------------------------------------ 256 x 256 x 32 tiling
+// ------------------------------------------------------------------ 256 x 256 x 64 tiling
 namespace big {
 
 constexpr int BM = 256, BN = 256, BK = 64;
