@@ -32,6 +32,10 @@ def parse():
     ap.add_argument("--host-blocks", type=int, default=6,
                     help="streamed configs: number of distinct real-shape pinned host blocks; the layers cycle through them "
                          "(the full 175B model needs 348 GB of pinned memory, more than a box may pin)")
+    ap.add_argument("--mode", default="fused", choices=["fused", "literal"],
+                    help="fused: W+- = rn(theta +- eps z) staged, theta untouched, both signs in one batched pass (default); "
+                         "literal: Alg. 1 as printed, theta perturbed in place (+eps, -2 eps, +eps) with one forward after each "
+                         "of the first two (resident configurations only)")
     ap.add_argument("--writeback-interval", type=int, default=1,
                     help="streamed configuration: write the updated blocks back to the host every K-th step (1 = every step, "
                          "the paper's schedule)")
@@ -204,8 +208,10 @@ def main():
     if streamed and args.writeback_interval != 1:
         zo_amd.zo_set_writeback_interval(h, args.writeback_interval)
 
+    mode = zo_amd.ZO_MODE_LITERAL if args.mode == "literal" else zo_amd.ZO_MODE_FUSED
+
     def step(i):
-        zo_amd.zo_step(h, tokens, c["batch"], c["seq"], i, c["eps"], c["lr"], zo_amd.ZO_MODE_FUSED, want_host=False)
+        zo_amd.zo_step(h, tokens, c["batch"], c["seq"], i, c["eps"], c["lr"], mode, want_host=False)
 
     for i in range(args.warmup):
         step(i)
@@ -226,7 +232,7 @@ def main():
         a.copy_(b)
         torch.cuda.synchronize()
         del a, b
-    lp, lm, g = zo_amd.zo_step(h, tokens, c["batch"], c["seq"], 10**6, c["eps"], c["lr"])
+    lp, lm, g = zo_amd.zo_step(h, tokens, c["batch"], c["seq"], 10**6, c["eps"], c["lr"], mode)
     flags = zo_amd.zo_device_flags(h)
     zo_amd.zo_free(h)
 
@@ -276,7 +282,7 @@ def main():
         "dtype": dname, "data": "synthetic",
         "config": {"workload": args.config, "n_layers": c["n_layers"], "d_model": c["d_model"], "n_heads": c["n_heads"],
                    "d_ffn": c["d_ffn"], "vocab": c["vocab"], "batch": c["batch"], "seq_len": c["seq"], "eps": c["eps"],
-                   "lr": c["lr"], "mode": "fused", "update_rounding": "stochastic" if args.stochastic_update else "nearest",
+                   "lr": c["lr"], "mode": args.mode, "update_rounding": "stochastic" if args.stochastic_update else "nearest",
                    "residency": "pinned-host blocks, streamed" if streamed else "hbm"},
         "roofline": roof,
         "kernels": kernels,
