@@ -72,6 +72,24 @@ def test_attention_at_13b_shape_sampled_heads():
         assert np.max(np.abs(got - want)) < 3 * 2.0**-8 * (1 + np.abs(want).max())
 
 
+@pytest.mark.parametrize("seq", [8192, 4100])
+def test_attention_long_context_sampled_heads(seq):
+    """The longer-context variants (8192 tokens; 4100 leaves a ragged last key tile and query block): whole heads
+    against the oracle, which costs it O(S^2 d) per head only."""
+    n_seq, heads = 2, 4
+    d = heads * DH
+    g = _gen(13 + seq)
+    qkv = torch.randn(n_seq * seq, 3 * d, device=DEV, generator=g).to(torch.bfloat16)
+    out = torch.zeros(n_seq * seq, d, device=DEV, dtype=torch.bfloat16)
+    zo_amd.zo_kernel_attention(qkv, out, BF, n_seq, seq, heads, DH)
+    for sq, head in [(0, 0), (1, 3)]:
+        blk = qkv[sq * seq:(sq + 1) * seq]
+        q, k, v = (_wide(blk[:, o * d + head * DH:o * d + (head + 1) * DH])[None] for o in range(3))
+        want = zo.causal_attention(q, k, v, 1)[0]
+        got = _wide(out[sq * seq:(sq + 1) * seq, head * DH:(head + 1) * DH])
+        assert np.max(np.abs(got - want)) < 3 * 2.0**-8 * (1 + np.abs(want).max())
+
+
 def test_layernorm_and_update_streams_at_13b_sizes_sampled():
     g = _gen(12)
     h = torch.randn(2 * M_HALF, D, device=DEV, generator=g) * 2 + 0.3
