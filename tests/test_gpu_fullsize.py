@@ -120,3 +120,43 @@ def test_layernorm_and_update_streams_at_13b_sizes_sampled():
         assert zo.axpy_z(one, BF, 2**40 + 3, 654, -2e-3, first=int(i))[0] == got[j]
         assert zo.axpy_z(one, BF, 99, 654, 1e-3, first=int(i))[0] == got_p[j]
         assert zo.axpy_z(one, BF, 99, 654, -np.float32(1e-3), first=int(i))[0] == got_m[j]
+
+
+def test_step_invariants_at_opt_1_3b_size():
+    """A whole OPT-1.3B-shaped model (the oracle cannot run it): the step is a deterministic function of
+    (theta, tokens, seed); lr = 0 leaves every parameter bit for bit; a step with lr > 0 moves theta and changes
+    the next step's losses; losses sit near ln V for the synthetic initialisation."""
+    c = dict(zi.CONFIGS["opt-1.3b"])
+    shapes = zi.tensor_shapes(c["n_layers"], c["d_model"], c["d_ffn"], c["vocab"], c["max_pos"])
+    g = _gen(21)
+    tensors = []
+    for name, shape in shapes:
+        leaf = name.split(".")[-1]
+        if len(shape) == 2:
+            tensors.append((0.02 * torch.randn(shape, device=DEV, generator=g)).to(torch.bfloat16))
+        elif leaf.endswith("_g"):
+            tensors.append(torch.ones(shape, device=DEV, dtype=torch.bfloat16))
+        else:
+            tensors.append(torch.zeros(shape, device=DEV, dtype=torch.bfloat16))
+    batch, seq = 2, 1024
+    tokens = torch.randint(0, c["vocab"], (batch, seq), dtype=torch.int32, device=DEV, generator=g)
+    cfg = zo_amd.make_config(c["n_layers"], c["d_model"], c["n_heads"], c["d_ffn"], c["vocab"], c["max_pos"], BF)
+    nbytes = zo_amd.zo_workspace_bytes(cfg, batch, seq)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    stream = torch.cuda.Stream(device=DEV)
+    torch.cuda.synchronize()
+    h = zo_amd.zo_init_model(cfg, tensors, ws, nbytes, batch, seq, stream, None)
+    before = [t.clone() for t in tensors]
+    a = zo_amd.zo_step(h, tokens, batch, seq, 5, 1e-3, 0.0)
+    b = zo_amd.zo_step(h, tokens, batch, seq, 5, 1e-3, 0.0)
+    assert a == b                                                       # same seed, same theta: same bits
+    assert all(torch.equal(x.view(torch.int16), y.view(torch.int16)) for x, y in zip(tensors, before))   # lr = 0
+    assert abs(a[0] / np.log(c["vocab"]) - 1) < 0.1 and abs(a[1] / np.log(c["vocab"]) - 1) < 0.1
+    other = zo_amd.zo_step(h, tokens, batch, seq, 6, 1e-3, 0.0)
+    assert other[2] != a[2]                                             # another direction, another g
+    zo_amd.zo_step(h, tokens, batch, seq, 5, 1e-3, 1e-2)                # a large step so that bf16 weights do move
+    assert any(not torch.equal(x.view(torch.int16), y.view(torch.int16)) for x, y in zip(tensors, before))
+    after = zo_amd.zo_step(h, tokens, batch, seq, 5, 1e-3, 0.0)
+    assert after != a
+    assert zo_amd.zo_device_flags(h) == 0
+    zo_amd.zo_free(h)

@@ -56,7 +56,8 @@ def _closed_form(ra, rb):
 def test_counter_layout_words_to_elements():
     # element 4j+l of tensor t under seed s comes from Philox(counter=(j lo, j hi, t, 0), key=(s lo, s hi)):
     # words (0,1) -> elements 4j, 4j+1 ; words (2,3) -> elements 4j+2, 4j+3
-    for seed, t, j in [(42, 0, 0), (42, 0, 1), (42, 1, 0), (2**40 + 5, 33, 2**31 + 3), (7, 66, 12345)]:
+    for seed, t, j in [(42, 0, 0), (42, 0, 1), (42, 1, 0), (2**40 + 5, 33, 2**31 + 3), (7, 66, 12345),
+                       (9, 2, 2**33 + 5), (2**63 + 1, 1921, 2**35 + 2**32 - 1)]:      # block index beyond 32 bits: the counter's second word
         w = philox_ints.words_for(seed, t, j)
         z = zo.z_values(seed, t, 4 * j, 4)
         for pair in range(2):
