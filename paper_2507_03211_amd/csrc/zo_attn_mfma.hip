@@ -61,7 +61,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: 
 
 template <int DT, int DH>
 __global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(const uint16_t *__restrict__ qkv, uint16_t *__restrict__ out, int seq,
-                                                        int n_heads)
+                                                        int n_heads, int n_seq)
 {
     constexpr int CH = DH / 8;            // 16-byte chunks per K / V row
     // K and V tiles, both [key][channel] as they sit in memory, 16-byte chunks XOR-swizzled per key so that
@@ -74,8 +74,17 @@ __global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(cons
     auto kswz = [](int r) { return DH == 128 ? (r & 15) : ((r >> 1) & 7); };
     auto vswz = [](int r) { return DH == 128 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); };
 
-    const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;             // long rows first
-    const int head = blockIdx.y, sq = blockIdx.z;
+    // Workgroup -> (query tile, head, sequence).  The hardware deals consecutive workgroups round-robin to the 8
+    // XCDs, so workgroup w runs on XCD w % 8 and is that XCD's (w / 8)-th.  Every (head, sequence) pair goes to one
+    // XCD with all its query tiles, long rows first: the XCDs then hold equal shares of the causal triangle (dealing
+    // the query tiles round-robin would give one XCD the two longest of every 16 and another the two shortest), and
+    // the K and V of a pair are fetched into one L2 instead of eight.  The grid is padded to whole rounds of 8 pairs.
+    const int n_qt = (seq + BQ - 1) / BQ;
+    const int slot = (int)blockIdx.x >> 3;
+    const int pair = (slot / n_qt) * 8 + ((int)blockIdx.x & 7);
+    if (pair >= n_heads * n_seq) return;
+    const int qt = n_qt - 1 - slot % n_qt;
+    const int head = pair % n_heads, sq = pair / n_heads;
     const int d = n_heads * DH, ld = 3 * d;
     const uint16_t *base = qkv + (size_t)sq * seq * ld + head * DH;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -331,15 +340,18 @@ hipError_t launch_attention_mfma(const void *qkv, void *out, int dtype, int n_se
                                  hipStream_t s)
 {
     if (!mfma_attention_supported(seq, d_head) || (dtype != kBF16 && dtype != kFP16)) return hipErrorInvalidValue;
-    const dim3 grid((seq + BQ - 1) / BQ, n_heads, n_seq), block(256);
+    const long long pairs8 = ((long long)n_heads * n_seq + 7) / 8 * 8;
+    const long long n_wg = pairs8 * ((seq + BQ - 1) / BQ);
+    if (n_heads < 1 || n_seq < 1 || n_wg > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)n_wg), block(256);
     const uint16_t *q = (const uint16_t *)qkv;
     uint16_t *o = (uint16_t *)out;
     if (dtype == kBF16) {
-        if (d_head == 64) attn_mfma_kernel<kBF16, 64><<<grid, block, 0, s>>>(q, o, seq, n_heads);
-        else attn_mfma_kernel<kBF16, 128><<<grid, block, 0, s>>>(q, o, seq, n_heads);
+        if (d_head == 64) attn_mfma_kernel<kBF16, 64><<<grid, block, 0, s>>>(q, o, seq, n_heads, n_seq);
+        else attn_mfma_kernel<kBF16, 128><<<grid, block, 0, s>>>(q, o, seq, n_heads, n_seq);
     } else {
-        if (d_head == 64) attn_mfma_kernel<kFP16, 64><<<grid, block, 0, s>>>(q, o, seq, n_heads);
-        else attn_mfma_kernel<kFP16, 128><<<grid, block, 0, s>>>(q, o, seq, n_heads);
+        if (d_head == 64) attn_mfma_kernel<kFP16, 64><<<grid, block, 0, s>>>(q, o, seq, n_heads, n_seq);
+        else attn_mfma_kernel<kFP16, 128><<<grid, block, 0, s>>>(q, o, seq, n_heads, n_seq);
     }
     return hipGetLastError();
 }
