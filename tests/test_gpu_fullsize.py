@@ -90,6 +90,28 @@ def test_attention_long_context_sampled_heads(seq):
         assert np.max(np.abs(got - want)) < 3 * 2.0**-8 * (1 + np.abs(want).max())
 
 
+@pytest.mark.parametrize("n_seq,seq,heads,dh", [(2, 1024, 40, 128), (2, 1100, 48, 64), (3, 300, 5, 128)])
+def test_attention_work_list_covers_every_item(n_seq, seq, heads, dh):
+    """More (query tile, head, sequence) items than resident workgroups: several rounds over the per-XCD item list,
+    a last group of fewer pairs, and a pair count that does not fill the 8 XCDs evenly.  Every output row must have
+    been written (they start as NaN), the first row of every head is v[0] itself (one key, probability 1), and
+    sampled heads, the last pair among them, are compared with the oracle."""
+    d = heads * dh
+    g = _gen(17 + seq)
+    qkv = torch.randn(n_seq * seq, 3 * d, device=DEV, generator=g).to(torch.bfloat16)
+    out = torch.full((n_seq * seq, d), float("nan"), device=DEV, dtype=torch.bfloat16)
+    zo_amd.zo_kernel_attention(qkv, out, BF, n_seq, seq, heads, dh)
+    assert not bool(torch.isnan(out).any())
+    first = out.view(n_seq, seq, d)[:, 0]
+    assert bool((first == qkv.view(n_seq, seq, 3 * d)[:, 0, 2 * d:]).all())
+    for sq, head in [(0, 0), (n_seq // 2, heads // 2), (n_seq - 1, heads - 1)]:
+        blk = qkv[sq * seq:(sq + 1) * seq]
+        q, k, v = (_wide(blk[:, o * d + head * dh:o * d + (head + 1) * dh])[None] for o in range(3))
+        want = zo.causal_attention(q, k, v, 1)[0]
+        got = _wide(out[sq * seq:(sq + 1) * seq, head * dh:(head + 1) * dh])
+        assert np.max(np.abs(got - want)) < 3 * 2.0**-8 * (1 + np.abs(want).max())
+
+
 def test_layernorm_and_update_streams_at_13b_sizes_sampled():
     g = _gen(12)
     h = torch.randn(2 * M_HALF, D, device=DEV, generator=g) * 2 + 0.3
