@@ -41,6 +41,10 @@ def parse():
                          "the paper's schedule)")
     ap.add_argument("--stochastic-update", action="store_true",
                     help="round the update of Eq. 2 stochastically into the 16-bit storage type (opt-in variant)")
+    ap.add_argument("--update", default="immediate", choices=["deferred", "immediate"],
+                    help="resident fused mode: 'deferred' applies a step's update inside the next step's staging pass (Alg. 2's "
+                         "order; the last one is flushed inside the timed region), 'immediate' in a pass of its own at the end "
+                         "of the step; theta ends up bit-identical either way")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy, a kernel of known HBM traffic that calibrates "
@@ -209,12 +213,17 @@ def main():
         zo_amd.zo_set_writeback_interval(h, args.writeback_interval)
 
     mode = zo_amd.ZO_MODE_LITERAL if args.mode == "literal" else zo_amd.ZO_MODE_FUSED
+    deferred = (not streamed) and mode == zo_amd.ZO_MODE_FUSED and args.update == "deferred"
+    if deferred:
+        zo_amd.zo_set_deferred_update(h, 1)
 
     def step(i):
         zo_amd.zo_step(h, tokens, c["batch"], c["seq"], i, c["eps"], c["lr"], mode, want_host=False)
 
     for i in range(args.warmup):
         step(i)
+    if deferred:
+        zo_amd.zo_flush_pending(h)          # the timed region starts with nothing pending and ends the same way
     torch.cuda.synchronize()
     launches_per_step = 16 * c["n_layers"] + 64 + 4 * ((2 * c["batch"] * c["seq"]) // 2048 + 2)
     zo_amd.zo_profile_begin(h, launches_per_step * args.steps)
@@ -222,6 +231,8 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i)
+    if deferred:
+        zo_amd.zo_flush_pending(h)          # the last step's update: every one of the K updates lies inside the timed region
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = zo_amd.zo_profile_end(h)
@@ -283,6 +294,8 @@ def main():
         "config": {"workload": args.config, "n_layers": c["n_layers"], "d_model": c["d_model"], "n_heads": c["n_heads"],
                    "d_ffn": c["d_ffn"], "vocab": c["vocab"], "batch": c["batch"], "seq_len": c["seq"], "eps": c["eps"],
                    "lr": c["lr"], "mode": args.mode, "update_rounding": "stochastic" if args.stochastic_update else "nearest",
+                   "update": ("deferred: applied in the next step's staging pass, the last one flushed inside the timed region"
+                              if deferred else "deferred per block (Alg. 2 / Alg. 3)" if streamed else "immediate"),
                    "residency": "pinned-host blocks, streamed" if streamed else "hbm"},
         "roofline": roof,
         "kernels": kernels,

@@ -118,7 +118,7 @@ int zo_dual_forward(zo_model *m, const int32_t *tokens, int batch, int seq, uint
 
 /* One whole step: zo_dual_forward, g = (l+ - l-)/(2 eps) and s = -(lr g) on the device,
  * then theta <- rn(fma(s, z, theta)) for every tensor.  A non-finite g skips the update
- * (s = 0).  ZO_RESIDENT: the update is applied at once.  ZO_STREAMED (Alg. 2 / Alg. 3):
+ * (s = 0).  ZO_RESIDENT: the update is applied at once (unless zo_set_deferred_update).  ZO_STREAMED (Alg. 2 / Alg. 3):
  * blocks are uploaded one ahead of the computation, each block's update from the previous
  * step is applied right after its upload and written back, and this step's update stays
  * pending until the next zo_step or zo_flush_pending.
@@ -147,8 +147,19 @@ int zo_stream_begin(zo_model *m, const int32_t *tokens, int batch, int seq, uint
 int zo_stream_end(zo_model *m, float lr, double *host_g, double *host_loss_pm);
 
 /* Apply the updates that the host copies of a streamed model still lack (as printed, Alg. 2 never
- * applies the last one) and write every block back.  No-op when nothing is pending. */
+ * applies the last one) and write every block back; for a resident model with deferred updates, apply the
+ * pending one.  No-op when nothing is pending. */
 int zo_flush_pending(zo_model *m);
+
+/* Resident model: defer the update of Eq. 2 the way Alg. 2 does.  With `on` non-zero a ZO_MODE_FUSED zo_step computes
+ * L+-, g and the step scalar, and leaves theta as it was: the update theta <- rn(theta + s z) is applied by the next
+ * zo_step / zo_dual_forward in ZO_MODE_FUSED, inside the staging pass that reads every parameter anyway (one read
+ * and one write of theta less per step, the same bits in theta afterwards), or by zo_flush_pending.  Until then
+ * the caller's tensors are one update behind.  zo_perturb and the ZO_MODE_LITERAL paths apply a pending update
+ * first; a ZO_MODE_LITERAL zo_step updates at once, as without this setting.  The rounding mode of a pending update
+ * is the one that was set when its step ran.  `on` == 0 applies what is pending and returns to immediate updates.
+ * ZO_ESTATE for a streamed model (it always defers). */
+int zo_set_deferred_update(zo_model *m, int on);
 
 /* Streamed models: how often the updated blocks go back to pinned host memory.  1 (the default) is Alg. 3 as
  * printed: every block is written back in every step, so the host link carries each block both ways.  With
@@ -217,6 +228,15 @@ int zo_kernel_axpy_z_sr(const void *src, void *dst, int dtype, uint64_t n, uint6
  * transposed ([cols, rows], the layout the GEMMs read) when `transpose` is non-zero. */
 int zo_kernel_stage_pm(const void *theta, void *w_plus, void *w_minus, int dtype, int rows, int cols,
                        int transpose, uint64_t seed, uint32_t tensor_id, float eps, void *stream);
+
+/* The staging pass with a pending update of Eq. 2 folded in: first theta <- rn(fma(*dev_scale, z', theta)) in place,
+ * z' drawn from `upd_seed` (round to nearest, or stochastic rounding with the words of stream 3 when `stochastic` is
+ * non-zero: 16-bit types only), then W+- = rn(theta +- eps z) from the updated theta, z drawn from `seed`, as
+ * zo_kernel_stage_pm writes them.  theta, w_plus, w_minus: device, 16-byte aligned; dev_scale: one float on the
+ * device.  The same bits as zo_kernel_axpy_z(_sr) followed by zo_kernel_stage_pm. */
+int zo_kernel_stage_update_pm(void *theta, void *w_plus, void *w_minus, int dtype, int rows, int cols, int transpose,
+                              uint64_t seed, uint32_t tensor_id, float eps, uint64_t upd_seed,
+                              const float *dev_scale, int stochastic, void *stream);
 
 /* Sign-batched linear layer:  rows [0, m_half) of x use (wt_plus, b_plus), rows
  * [m_half, 2 m_half) use (wt_minus, b_minus):  y = x W + b with W given transposed as

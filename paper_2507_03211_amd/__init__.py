@@ -21,9 +21,9 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 
 EXPORTS = (
     "zo_workspace_bytes", "zo_init_model", "zo_perturb", "zo_dual_forward", "zo_step", "zo_stream_block",
-    "zo_stream_begin", "zo_stream_end", "zo_flush_pending", "zo_set_writeback_interval", "zo_set_update_rounding", "zo_device_flags", "zo_free",
+    "zo_stream_begin", "zo_stream_end", "zo_flush_pending", "zo_set_writeback_interval", "zo_set_deferred_update", "zo_set_update_rounding", "zo_device_flags", "zo_free",
     "zo_last_error", "zo_profile_begin", "zo_profile_end",
-    "zo_kernel_z", "zo_kernel_normal_pairs", "zo_kernel_axpy_z", "zo_kernel_axpy_z_sr", "zo_kernel_stage_pm", "zo_kernel_linear_pm",
+    "zo_kernel_z", "zo_kernel_normal_pairs", "zo_kernel_axpy_z", "zo_kernel_axpy_z_sr", "zo_kernel_stage_pm", "zo_kernel_stage_update_pm", "zo_kernel_linear_pm",
     "zo_kernel_layernorm_pm", "zo_kernel_attention", "zo_kernel_lmhead_scratch_bytes", "zo_kernel_lmhead_ce",
 )
 
@@ -67,6 +67,7 @@ def lib():
         L.zo_flush_pending.argtypes = [vp]
         L.zo_set_update_rounding.argtypes = [vp, i32]
         L.zo_set_writeback_interval.argtypes = [vp, i32]
+        L.zo_set_deferred_update.argtypes = [vp, i32]
         L.zo_device_flags.argtypes = [vp, ctypes.POINTER(u32)]
         L.zo_free.argtypes = [vp]
         L.zo_profile_begin.argtypes = [vp, i32]
@@ -76,6 +77,7 @@ def lib():
         L.zo_kernel_axpy_z.argtypes = [vp, vp, i32, u64, u64, u32, f32, vp, vp]
         L.zo_kernel_axpy_z_sr.argtypes = [vp, vp, i32, u64, u64, u32, f32, vp, vp]
         L.zo_kernel_stage_pm.argtypes = [vp, vp, vp, i32, i32, i32, i32, u64, u32, f32, vp]
+        L.zo_kernel_stage_update_pm.argtypes = [vp, vp, vp, i32, i32, i32, i32, u64, u32, f32, u64, vp, i32, vp]
         L.zo_kernel_linear_pm.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.zo_kernel_layernorm_pm.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]
         L.zo_kernel_attention.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
@@ -175,6 +177,10 @@ def zo_set_writeback_interval(model, steps):
     _check(lib().zo_set_writeback_interval(model, steps))
 
 
+def zo_set_deferred_update(model, on):
+    _check(lib().zo_set_deferred_update(model, int(on)))
+
+
 def zo_set_update_rounding(model, mode):
     _check(lib().zo_set_update_rounding(model, mode))
 
@@ -223,6 +229,12 @@ def zo_kernel_axpy_z_sr(src, dst, dtype, n, seed, tensor_id, scale, dev_scale=No
 def zo_kernel_stage_pm(theta, w_plus, w_minus, dtype, rows, cols, transpose, seed, tensor_id, eps, stream=None):
     _check(lib().zo_kernel_stage_pm(_ptr(theta), _ptr(w_plus), _ptr(w_minus), dtype, rows, cols, int(transpose), seed,
                                     tensor_id, eps, _stream(stream)))
+
+
+def zo_kernel_stage_update_pm(theta, w_plus, w_minus, dtype, rows, cols, transpose, seed, tensor_id, eps, upd_seed, dev_scale,
+                              stochastic=False, stream=None):
+    _check(lib().zo_kernel_stage_update_pm(_ptr(theta), _ptr(w_plus), _ptr(w_minus), dtype, rows, cols, int(transpose), seed,
+                                           tensor_id, eps, upd_seed, _ptr(dev_scale), int(stochastic), _stream(stream)))
 
 
 def zo_kernel_linear_pm(x, wt_plus, wt_minus, b_plus, b_minus, y, dtype, m_half, n, k, epilogue, stream=None):

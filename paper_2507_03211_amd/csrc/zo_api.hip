@@ -175,6 +175,11 @@ struct zo_model {
     uint64_t pend_seed[kMaxPending];
     bool resident_pending;
     int update_rounding;               // ZO_ROUND_*: how the update of Eq. 2 goes into a 16-bit type
+    // Resident model with deferred updates (Alg. 2's order on one GPU): a fused-mode step leaves its update pending
+    // (pend_n = 1, pend_seed[0], s_pend[0], rounded as pend_round says) and the next staging pass over theta
+    // applies it on the way.
+    bool deferred;
+    int pend_round;
     bool step_open;
     int next_block;
     uint64_t step_seed;
@@ -256,26 +261,38 @@ struct BlockPtrs {   // staged parameter pointers of one block, per sign
 };
 
 // Stage the embeddings and the final LayerNorm: W+- copies (fused) or nothing (literal reads theta itself).
-int stage_globals(zo_model *m, int seq, uint64_t seed, float eps)
+// upd_mode != 0: a pending update (seed m->pend_seed[0], scalar m->s_pend[0]) is applied to these tensors on the way.
+// Only the first `seq` position rows are staged, so the position table takes its update in a pass of its own.
+int stage_globals(zo_model *m, int seq, uint64_t seed, float eps, int upd_mode)
 {
     const zo_config &c = m->cfg;
-    StageBatch b{};
+    StageBatch b{}, bpos{};
     const int lnf = 2 + kPerBlock * c.n_layers;
     const size_t e = elem_bytes(c.dtype);
     stage_batch_add(b, m->tptr[0], m->ws + m->wsp.e_pm[0], m->ws + m->wsp.e_pm[1], c.vocab, c.d_model, 0, false);
-    stage_batch_add(b, m->tptr[1], m->ws + m->wsp.pos_pm[0], m->ws + m->wsp.pos_pm[1], seq, c.d_model, 1, false);
+    stage_batch_add(upd_mode ? bpos : b, m->tptr[1], m->ws + m->wsp.pos_pm[0], m->ws + m->wsp.pos_pm[1], seq, c.d_model, 1, false);
     stage_batch_add(b, m->tptr[lnf], m->ws + m->wsp.lnf_pm[0], m->ws + m->wsp.lnf_pm[1], 1, c.d_model, lnf, false);
     stage_batch_add(b, m->tptr[lnf + 1], m->ws + m->wsp.lnf_pm[0] + c.d_model * e, m->ws + m->wsp.lnf_pm[1] + c.d_model * e, 1,
                     c.d_model, lnf + 1, false);
-    const double bytes = 3.0 * e * ((double)c.vocab * c.d_model + (double)seq * c.d_model + 2.0 * c.d_model);
-    ZO_PROF(m, K_STAGE, bytes, launch_stage(b, c.dtype, seed, eps, false, m->compute));
+    const double n_rest = (double)c.vocab * c.d_model + 2.0 * c.d_model, n_pos = (double)seq * c.d_model;
+    if (upd_mode) {
+        const int keep = m->update_rounding;           // the rounding the pending step asked for
+        m->update_rounding = m->pend_round;
+        const int rc = axpy_range(m, 1, 1, m->pend_seed[0], 0.0f, m->s_pend, true);
+        m->update_rounding = keep;
+        ZO_TRY(rc);
+        ZO_PROF(m, K_STAGE, 4.0 * e * n_rest, launch_stage(b, c.dtype, seed, eps, false, m->compute, upd_mode, m->pend_seed[0], m->s_pend));
+        ZO_PROF(m, K_STAGE, 3.0 * e * n_pos, launch_stage(bpos, c.dtype, seed, eps, false, m->compute));
+    } else {
+        ZO_PROF(m, K_STAGE, 3.0 * e * (n_rest + n_pos), launch_stage(b, c.dtype, seed, eps, false, m->compute));
+    }
     return ZO_OK;
 }
 
 // Stage one block into the per-sign scratch.  `slot_base` == nullptr: the block's 16 tensors are read
 // where the caller keeps them (resident model, separately allocated); otherwise from a device copy of
 // the block laid out contiguously in canonical order (streamed model).
-int stage_block(zo_model *m, int layer, const char *slot_base, uint64_t seed, float eps, bool single)
+int stage_block(zo_model *m, int layer, const char *slot_base, uint64_t seed, float eps, bool single, int upd_mode = 0)
 {
     const zo_config &c = m->cfg;
     const BlockLayout &L = m->lay;
@@ -294,7 +311,8 @@ int stage_block(zo_model *m, int layer, const char *slot_base, uint64_t seed, fl
     add(T_LN2G, L.st_ln2g, false); add(T_LN2B, L.st_ln2b, false);
     add(T_W1, L.st_w1, true); add(T_B1, L.st_b1, false);
     add(T_W2, L.st_w2, true); add(T_B2, L.st_b2, false);
-    ZO_PROF(m, K_STAGE, (single ? 2.0 : 3.0) * e * (double)L.total, launch_stage(b, c.dtype, seed, eps, single, m->compute));
+    ZO_PROF(m, K_STAGE, (single ? 2.0 : upd_mode ? 4.0 : 3.0) * e * (double)L.total,
+            launch_stage(b, c.dtype, seed, eps, single, m->compute, upd_mode, m->pend_seed[0], m->s_pend));
     return ZO_OK;
 }
 
@@ -397,13 +415,16 @@ int embed(zo_model *m, const int32_t *tokens, int n_sign, int batch, int seq, co
 int forward_fused_resident(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t seed, float eps)
 {
     const zo_config &c = m->cfg;
-    ZO_TRY(stage_globals(m, seq, seed, eps));
+    // a pending update (deferred mode) rides on this step's staging passes: every parameter is read here anyway
+    const int upd_mode = m->pend_n > 0 ? (m->pend_round == ZO_ROUND_STOCHASTIC ? 2 : 1) : 0;
+    ZO_TRY(stage_globals(m, seq, seed, eps, upd_mode));
     const char *ep = m->ws + m->wsp.e_pm[0], *em = m->ws + m->wsp.e_pm[1];
     ZO_TRY(embed(m, tokens, 2, batch, seq, ep, em, m->ws + m->wsp.pos_pm[0], m->ws + m->wsp.pos_pm[1]));
     for (int l = 0; l < c.n_layers; ++l) {
-        ZO_TRY(stage_block(m, l, nullptr, seed, eps, false));
+        ZO_TRY(stage_block(m, l, nullptr, seed, eps, false, upd_mode));
         ZO_TRY(block_forward(m, 2, batch, seq));
     }
+    m->pend_n = 0;
     return head_and_loss(m, 2, batch, seq, ep, em, m->ws + m->wsp.lnf_pm[0], m->ws + m->wsp.lnf_pm[1], m->loss_pm);
 }
 
@@ -516,7 +537,7 @@ int stream_begin(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_
         ZO_TRY(axpy_range(m, lnf, 2, m->pend_seed[m->pend_n - 1], 0.0f, m->s_pend + (m->pend_n - 1), true));
         m->resident_pending = false;
     }
-    ZO_TRY(stage_globals(m, seq, seed, eps));
+    ZO_TRY(stage_globals(m, seq, seed, eps, 0));
     ZO_TRY(embed(m, tokens, 2, batch, seq, m->ws + m->wsp.e_pm[0], m->ws + m->wsp.e_pm[1], m->ws + m->wsp.pos_pm[0],
                  m->ws + m->wsp.pos_pm[1]));
     m->step_open = true;
@@ -603,7 +624,7 @@ extern "C" int zo_init_model(const zo_config *cfg, void *const *tensor_ptrs, int
     hipError_t err = hipMemcpy(m->ws + wsp.descs, m->descs.data(), sizeof(TensorDesc) * n_tensors, hipMemcpyHostToDevice);
     if (err == hipSuccess) err = hipMemset(sc, 0, 256);
     if (err != hipSuccess) { delete m; return fail(ZO_EHIP, "initialising the workspace failed: %s", hipGetErrorString(err)); }
-    m->wb_interval = 1; m->pend_n = 0; m->resident_pending = false; m->step_open = false; m->next_block = 0; m->prof_on = false; m->prof_n = 0;
+    m->wb_interval = 1; m->pend_n = 0; m->resident_pending = false; m->deferred = false; m->pend_round = ZO_ROUND_NEAREST; m->step_open = false; m->next_block = 0; m->prof_on = false; m->prof_n = 0;
     for (int s = 0; s < 2; ++s) {
         m->slot_block[s] = -1; m->slot_state[s] = SLOT_EMPTY; m->slot_dirty[s] = false;
         m->ev_uploaded[s] = m->ev_staged[s] = m->ev_written[s] = nullptr;
@@ -641,6 +662,21 @@ extern "C" int zo_free(zo_model *m)
     return ZO_OK;
 }
 
+namespace {
+// Resident model, deferred mode: bring theta up to date with the plain update pass (anything that reads or writes
+// theta outside the fused staging calls this first).
+int apply_pending_resident(zo_model *m)
+{
+    if (m->cfg.residency != ZO_RESIDENT || m->pend_n == 0) return ZO_OK;
+    const int keep = m->update_rounding;
+    m->update_rounding = m->pend_round;
+    const int rc = axpy_range(m, 0, m->n_tensors, m->pend_seed[0], 0.0f, m->s_pend, true);
+    m->update_rounding = keep;
+    if (rc == ZO_OK) m->pend_n = 0;
+    return rc;
+}
+}
+
 extern "C" int zo_perturb(zo_model *m, uint64_t seed, float scale, int first_tensor, int n_tensors)
 {
     if (!m) return fail(ZO_EINVAL, "model is NULL");
@@ -649,6 +685,7 @@ extern "C" int zo_perturb(zo_model *m, uint64_t seed, float scale, int first_ten
     if (m->cfg.residency == ZO_STREAMED)
         for (int t = first_tensor; t < first_tensor + n_tensors; ++t)
             if (is_block_tensor(m, t)) return fail(ZO_ESTATE, "tensor %d lives in host memory; use the streamed step", t);
+    ZO_TRY(apply_pending_resident(m));
     return axpy_range(m, first_tensor, n_tensors, seed, scale, nullptr);
 }
 
@@ -663,6 +700,7 @@ extern "C" int zo_dual_forward(zo_model *m, const int32_t *tokens, int batch, in
     if (mode == ZO_MODE_FUSED) {
         ZO_TRY(forward_fused_resident(m, tokens, batch, seq, seed, eps));
     } else {
+        ZO_TRY(apply_pending_resident(m));
         ZO_TRY(axpy_range(m, 0, m->n_tensors, seed, eps, nullptr));
         ZO_TRY(forward_single(m, tokens, batch, seq, 0));
         ZO_TRY(axpy_range(m, 0, m->n_tensors, seed, -2.0f * eps, nullptr));
@@ -685,8 +723,15 @@ extern "C" int zo_step(zo_model *m, const int32_t *tokens, int batch, int seq, u
     if (!(eps > 0.0f)) return fail(ZO_EINVAL, "eps must be positive");
     if (m->cfg.residency == ZO_RESIDENT) {
         ZO_TRY(zo_dual_forward(m, tokens, batch, seq, seed, eps, mode, nullptr, nullptr));
-        ZO_HIP(launch_g_scalar(m->loss_pm, eps, lr, m->g, m->s_cur, m->flags, m->compute));
-        ZO_TRY(axpy_range(m, 0, m->n_tensors, seed, 0.0f, m->s_cur, true));
+        if (m->deferred && mode == ZO_MODE_FUSED) {       // Alg. 2: the update waits for the next pass over theta
+            ZO_HIP(launch_g_scalar(m->loss_pm, eps, lr, m->g, m->s_pend, m->flags, m->compute));
+            m->pend_seed[0] = seed;
+            m->pend_round = m->update_rounding;
+            m->pend_n = 1;
+        } else {
+            ZO_HIP(launch_g_scalar(m->loss_pm, eps, lr, m->g, m->s_cur, m->flags, m->compute));
+            ZO_TRY(axpy_range(m, 0, m->n_tensors, seed, 0.0f, m->s_cur, true));
+        }
         return read_back(m, host_g, host_loss_pm);
     }
     if (mode != ZO_MODE_FUSED) return fail(ZO_EINVAL, "a streamed model supports ZO_MODE_FUSED only");
@@ -747,6 +792,15 @@ extern "C" int zo_set_update_rounding(zo_model *m, int mode)
     return ZO_OK;
 }
 
+extern "C" int zo_set_deferred_update(zo_model *m, int on)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    if (m->cfg.residency != ZO_RESIDENT) return fail(ZO_ESTATE, "a streamed model always defers its updates");
+    if (!on) ZO_TRY(apply_pending_resident(m));
+    m->deferred = on != 0;
+    return ZO_OK;
+}
+
 extern "C" int zo_set_writeback_interval(zo_model *m, int steps)
 {
     if (!m) return fail(ZO_EINVAL, "model is NULL");
@@ -760,7 +814,8 @@ extern "C" int zo_set_writeback_interval(zo_model *m, int steps)
 extern "C" int zo_flush_pending(zo_model *m)
 {
     if (!m) return fail(ZO_EINVAL, "model is NULL");
-    if (m->cfg.residency != ZO_STREAMED || m->pend_n == 0) return ZO_OK;
+    if (m->cfg.residency == ZO_RESIDENT) return apply_pending_resident(m);
+    if (m->pend_n == 0) return ZO_OK;
     if (m->step_open) return fail(ZO_ESTATE, "a streamed step is open");
     const int lnf = 2 + kPerBlock * m->cfg.n_layers;
     if (m->resident_pending) {
@@ -872,6 +927,22 @@ extern "C" int zo_kernel_stage_pm(const void *theta, void *w_plus, void *w_minus
     StageBatch b{};
     stage_batch_add(b, theta, w_plus, w_minus, rows, cols, tensor_id, transpose != 0);
     ZO_HIP(launch_stage(b, dtype, seed, eps, false, (hipStream_t)stream));
+    return ZO_OK;
+}
+
+extern "C" int zo_kernel_stage_update_pm(void *theta, void *w_plus, void *w_minus, int dtype, int rows, int cols, int transpose,
+                                         uint64_t seed, uint32_t tensor_id, float eps, uint64_t upd_seed, const float *dev_scale,
+                                         int stochastic, void *stream)
+{
+    ZO_TRY(check_dtype(dtype));
+    if (!theta || !w_plus || !w_minus || !dev_scale) return fail(ZO_EINVAL, "NULL argument");
+    if (rows < 1 || cols < 1) return fail(ZO_EINVAL, "bad shape %d x %d", rows, cols);
+    if (transpose && cols % 4) return fail(ZO_EINVAL, "transposed staging needs cols %% 4 == 0");
+    if (stochastic && dtype == ZO_FP32) return fail(ZO_EINVAL, "stochastic rounding is for ZO_BF16 / ZO_FP16 storage");
+    if ((uintptr_t)theta % 16 || (uintptr_t)w_plus % 16 || (uintptr_t)w_minus % 16) return fail(ZO_EINVAL, "buffers must be 16-byte aligned");
+    StageBatch b{};
+    stage_batch_add(b, theta, w_plus, w_minus, rows, cols, tensor_id, transpose != 0);
+    ZO_HIP(launch_stage(b, dtype, seed, eps, false, (hipStream_t)stream, stochastic ? 2 : 1, upd_seed, dev_scale));
     return ZO_OK;
 }
 

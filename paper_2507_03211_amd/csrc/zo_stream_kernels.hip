@@ -208,17 +208,26 @@ __global__ __launch_bounds__(256) void axpy_z_multi_kernel(const TensorDesc *__r
 // Flat tiles copy kStageFlatTile consecutive elements; transposing tiles move a 64 x 64 patch
 // of a [rows, cols] matrix through LDS so that both the read (along cols) and the write
 // (along rows of the transposed result) are coalesced.
-template <int DT, bool SINGLE>
-__global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t seed, float eps)
+// UPD != 0: the pass first applies a pending update of Eq. 2 to theta itself, theta <- rn(fma(s, z', theta)) with z'
+// drawn from `upd_seed` and s read from dev_scale (UPD 1: round to nearest, 2: stochastic rounding), writes theta
+// back, and stages W+- from the updated value: Alg. 2's deferred update, in the pass that reads theta anyway.  The
+// arithmetic per element is that of axpy_z_kernel followed by the plain staging.
+template <int DT, bool SINGLE, int UPD>
+__global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t seed, float eps, uint64_t upd_seed,
+                                                    const float *__restrict__ dev_scale)
 {
     using W = typename Prec<DT>::W;
     constexpr int VN = Vec16<DT>::N;
+    static_assert(!(SINGLE && UPD != 0) && !(DT == kFP32 && UPD == 2), "no such variant");
+    float us = 0.0f;
+    if constexpr (UPD != 0) us = *dev_scale;
     int di = 0;
     for (int i = 1; i < batch.n; ++i)
         if (batch.d[i].first_tile <= blockIdx.x) di = i;
     const StageDesc &d = batch.d[di];
     const uint32_t tile = blockIdx.x - d.first_tile;
-    const W *__restrict__ src = (const W *)d.src;
+    W *const theta = (W *)const_cast<void *>(d.src);      // written only when UPD != 0
+    const W *src = theta;
     W *__restrict__ dp = (W *)d.dst_plus;
     W *__restrict__ dm = (W *)d.dst_minus;
     const uint64_t numel = (uint64_t)d.rows * d.cols;
@@ -234,29 +243,51 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
 #pragma unroll
                 for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b);
             }
-            if (i0 + VN <= numel) {
-                const uint4 raw = *(const uint4 *)(src + i0);
-                if constexpr (SINGLE) {
-                    *(uint4 *)(dp + i0) = raw;
+            const bool whole = i0 + VN <= numel;
+            if constexpr (SINGLE) {
+                if (whole) *(uint4 *)(dp + i0) = *(const uint4 *)(src + i0);
+                else for (int e = 0; e < VN && i0 + e < numel; ++e) dp[i0 + e] = src[i0 + e];
+            } else {
+                float th[VN], a[VN], b[VN];
+                if (whole) {
+                    unpack16<DT>(*(const uint4 *)(src + i0), th);
                 } else {
-                    float th[VN], a[VN], b[VN];
-                    unpack16<DT>(raw, th);
+                    for (int e = 0; e < VN; ++e) th[e] = i0 + e < numel ? Prec<DT>::w2f(src[i0 + e]) : 0.0f;
+                }
+                if constexpr (UPD != 0) {
+                    float zu[VN];
 #pragma unroll
-                    for (int e = 0; e < VN; ++e) {
-                        a[e] = __builtin_fmaf(eps, z[e], th[e]);
-                        b[e] = __builtin_fmaf(-eps, z[e], th[e]);
+                    for (int bk = 0; bk < VN / 4; ++bk) normal4(philox_block(upd_seed, d.tid, i0 / 4 + bk), zu + 4 * bk);
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(us, zu[e], th[e]);
+                    uint4 stored;
+                    if constexpr (UPD == 2) {
+                        uint32_t rw[VN];
+#pragma unroll
+                        for (int bk = 0; bk < VN / 4; ++bk) {
+                            const u32x4 r = philox_block(upd_seed, d.tid, i0 / 4 + bk, 3u);
+                            rw[4 * bk] = r.x; rw[4 * bk + 1] = r.y; rw[4 * bk + 2] = r.z; rw[4 * bk + 3] = r.w;
+                        }
+                        stored = pack16_sr<DT>(th, rw);
+                    } else {
+                        stored = pack16<DT>(th);
                     }
+                    unpack16<DT>(stored, th);          // staging starts from the stored value
+                    if (whole) *(uint4 *)(theta + i0) = stored;
+                    else for (int e = 0; e < VN && i0 + e < numel; ++e) theta[i0 + e] = Prec<DT>::f2w(th[e]);   // exact
+                }
+#pragma unroll
+                for (int e = 0; e < VN; ++e) {
+                    a[e] = __builtin_fmaf(eps, z[e], th[e]);
+                    b[e] = __builtin_fmaf(-eps, z[e], th[e]);
+                }
+                if (whole) {
                     *(uint4 *)(dp + i0) = pack16<DT>(a);
                     *(uint4 *)(dm + i0) = pack16<DT>(b);
-                }
-            } else {
-                for (int e = 0; e < VN && i0 + e < numel; ++e) {
-                    const float th = Prec<DT>::w2f(src[i0 + e]);
-                    if constexpr (SINGLE) {
-                        dp[i0 + e] = src[i0 + e];
-                    } else {
-                        dp[i0 + e] = Prec<DT>::f2w(__builtin_fmaf(eps, z[e], th));
-                        dm[i0 + e] = Prec<DT>::f2w(__builtin_fmaf(-eps, z[e], th));
+                } else {
+                    for (int e = 0; e < VN && i0 + e < numel; ++e) {
+                        dp[i0 + e] = Prec<DT>::f2w(a[e]);
+                        dm[i0 + e] = Prec<DT>::f2w(b[e]);
                     }
                 }
             }
@@ -289,6 +320,21 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
             } else {
                 float z[4];
                 normal4(philox_block(seed, d.tid, i0 / 4), z);
+                if constexpr (UPD != 0) {
+                    float zu[4];
+                    normal4(philox_block(upd_seed, d.tid, i0 / 4), zu);
+                    u32x4 r{};
+                    if constexpr (UPD == 2) r = philox_block(upd_seed, d.tid, i0 / 4, 3u);
+                    const uint32_t rw[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float v = __builtin_fmaf(us, zu[e], Prec<DT>::w2f(raw[e]));
+                        if constexpr (UPD == 2) raw[e] = DT == kBF16 ? sr_to_bf16(v, rw[e]) : sr_to_f16(v, rw[e]);
+                        else raw[e] = Prec<DT>::f2w(v);
+                    }
+                    if constexpr (sizeof(W) == 2) *(uint2 *)(theta + i0) = *(const uint2 *)raw;
+                    else *(uint4 *)(theta + i0) = *(const uint4 *)raw;
+                }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float th = Prec<DT>::w2f(raw[e]);
@@ -450,13 +496,18 @@ void stage_batch_add(StageBatch &b, const void *src, void *dp, void *dm, uint32_
     }
 }
 
-hipError_t launch_stage(const StageBatch &b, int dtype, uint64_t seed, float eps, bool single_copy, hipStream_t s)
+hipError_t launch_stage(const StageBatch &b, int dtype, uint64_t seed, float eps, bool single_copy, hipStream_t s, int upd_mode,
+                        uint64_t upd_seed, const float *dev_scale)
 {
     if (b.total_tiles == 0) return hipSuccess;
+    if (upd_mode < 0 || upd_mode > 2 || (upd_mode != 0 && (single_copy || !dev_scale)) || (upd_mode == 2 && dtype == kFP32))
+        return hipErrorInvalidValue;
     const dim3 grid(b.total_tiles), block(256);
-#define ZO_STAGE(DT)                                                                      \
-    if (single_copy) stage_kernel<DT, true><<<grid, block, 0, s>>>(b, seed, eps);          \
-    else stage_kernel<DT, false><<<grid, block, 0, s>>>(b, seed, eps);                     \
+#define ZO_STAGE(DT)                                                                                              \
+    if (single_copy) stage_kernel<DT, true, 0><<<grid, block, 0, s>>>(b, seed, eps, 0, nullptr);                   \
+    else if (upd_mode == 0) stage_kernel<DT, false, 0><<<grid, block, 0, s>>>(b, seed, eps, 0, nullptr);           \
+    else if (upd_mode == 1) stage_kernel<DT, false, 1><<<grid, block, 0, s>>>(b, seed, eps, upd_seed, dev_scale);  \
+    else if constexpr (DT != kFP32) stage_kernel<DT, false, 2><<<grid, block, 0, s>>>(b, seed, eps, upd_seed, dev_scale); \
     return hipGetLastError();
     switch (dtype) {
     case kFP32: ZO_STAGE(kFP32)
