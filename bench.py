@@ -32,6 +32,10 @@ def parse():
     ap.add_argument("--host-blocks", type=int, default=6,
                     help="streamed configs: number of distinct real-shape pinned host blocks; the layers cycle through them "
                          "(the full 175B model needs 348 GB of pinned memory, more than a box may pin)")
+    ap.add_argument("--hbm-blocks", type=int, default=0,
+                    help="streamed configs: keep this many of the blocks in device memory (each with memory of its own), spread "
+                         "evenly between the ones that are uploaded from pinned host memory for every visit; 0 = the paper's "
+                         "configuration, every block streamed")
     ap.add_argument("--mode", default="fused", choices=["fused", "literal"],
                     help="fused: W+- = rn(theta +- eps z) staged, theta untouched, both signs in one batched pass (default); "
                          "literal: Alg. 1 as printed, theta perturbed in place (+eps, -2 eps, +eps) with one forward after each "
@@ -193,9 +197,18 @@ def main():
             o += int(torch.Size(sh).numel())
         esz = host_ring.element_size()
         tensors = [resident[0], resident[1]]
+        n_host = c["n_layers"] - max(0, min(args.hbm_blocks, c["n_layers"]))
+        host_at = {int((i + 0.5) * c["n_layers"] / n_host) for i in range(n_host)}       # evenly spread
+        hbm_keep, nh = [], 0
         for l in range(c["n_layers"]):
-            base = host_ring.data_ptr() + (l % nring) * per_block * esz
-            tensors += [base + off * esz for off in offs]
+            if l in host_at:
+                base = host_ring.data_ptr() + (nh % nring) * per_block * esz
+                nh += 1
+                tensors += [base + off * esz for off in offs]
+            else:
+                blk = device_weights(torch, block_shapes, c["dtype"], dev, seed=100 + l)
+                hbm_keep.append(blk)
+                tensors += blk
         tensors += [resident[2], resident[3]]
     tokens = torch.randint(0, c["vocab"], (c["batch"], c["seq"]), dtype=torch.int32, device=dev,
                            generator=torch.Generator(device=dev).manual_seed(1))
@@ -305,10 +318,11 @@ def main():
         block_bytes = host_ring.shape[1] * host_ring.element_size()
         step_s = dt / args.steps
         out["streaming"] = {"block_bytes": block_bytes, "blocks_per_step": c["n_layers"], "distinct_host_blocks": int(host_ring.shape[0]),
-                            "h2d_gbs": block_bytes * c["n_layers"] / step_s / 1e9,
-                            "d2h_gbs": (block_bytes * c["n_layers"] / step_s / 1e9 / args.writeback_interval
+                            "h2d_gbs": block_bytes * n_host / step_s / 1e9,
+                            "d2h_gbs": (block_bytes * n_host / step_s / 1e9 / args.writeback_interval
                                         if args.warmup + args.steps > 1 else 0.0),
                             "writeback_interval": args.writeback_interval,
+                            "blocks_in_hbm": c["n_layers"] - n_host, "blocks_streamed": n_host,
                             "compute_ms_per_block": sum(v["ms_per_step"] for v in kernels.values()) / c["n_layers"],
                             "note": "layers cycle through the distinct host blocks, so values are not those of one model; "
                                     "traffic, kernels and schedule are those of the full model"}

@@ -70,10 +70,13 @@ typedef struct {
     int32_t n_layers, d_model, n_heads, d_ffn, vocab, max_pos;
     int32_t dtype;       /* ZO_FP32 / ZO_BF16 / ZO_FP16: storage type of every parameter */
     int32_t residency;   /* ZO_RESIDENT: all parameters in HBM.
-                            ZO_STREAMED: the 16 tensors of each block live in pinned host
-                            memory, one contiguous region per block in canonical order;
-                            embeddings and the final LayerNorm stay in HBM (Alg. 3 uploads
-                            only the blocks W_i). */
+                            ZO_STREAMED: the 16 tensors of a block live in pinned host
+                            memory, one contiguous region per block in canonical order, and are
+                            uploaded for every visit (Alg. 3 uploads only the blocks W_i);
+                            embeddings and the final LayerNorm stay in HBM.  Any block may be
+                            given in device memory instead (all 16 tensors; they need not be
+                            adjacent): it then stays in HBM and costs no transfer, so a model that
+                            does not fit streams only the blocks that HBM has no room for. */
     float   ln_eps;      /* LayerNorm epsilon (OPT: 1e-5) */
 } zo_config;
 
@@ -83,9 +86,10 @@ size_t zo_workspace_bytes(const zo_config *cfg, int batch, int seq);
 
 /* Create a model handle over caller-owned memory.
  *   tensor_ptrs[n_tensors]  canonical order.  ZO_RESIDENT: all device pointers.
- *                           ZO_STREAMED: ids 0, 1 and the last two are device pointers,
- *                           block tensors are pinned-host pointers, the 16 tensors of a
- *                           block adjacent in memory in canonical order.
+ *                           ZO_STREAMED: ids 0, 1 and the last two are device pointers;
+ *                           the 16 tensors of a block are either pinned-host pointers, adjacent
+ *                           in memory in canonical order, or all device pointers (the block
+ *                           stays in HBM).  Where a block lives is read off its pointers.
  *   workspace               device memory, >= zo_workspace_bytes(cfg, batch, seq), 256-byte aligned.
  *   compute_stream          hipStream_t on which all kernels run (NULL = the null stream).
  *   copy_stream             hipStream_t for host<->device block copies; required (and

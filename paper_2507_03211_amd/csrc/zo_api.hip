@@ -163,6 +163,12 @@ struct zo_model {
     float *s_cur, *s_pend;             // update scalars on the device: this step's (resident model), the pending steps' (streamed)
     uint32_t *flags;
     // streamed state
+    // A streamed model keeps every block where its pointers say: pinned host memory (uploaded for each visit, Alg. 3)
+    // or device memory (as many blocks as HBM has room for stay there and cost no transfer).  blk_dev[l]: block l is
+    // in device memory; blk_slot[l]: upload slot of a host block (its number among the host blocks, mod 2).
+    std::vector<char> blk_dev;
+    std::vector<int> blk_slot;
+    int up_next;                       // zo_step / zo_flush_pending: first block whose upload has not been enqueued yet
     hipEvent_t ev_uploaded[2], ev_staged[2], ev_written[2];
     int slot_block[2];
     SlotState slot_state[2];
@@ -462,7 +468,8 @@ int read_back(zo_model *m, double *host_g, double *host_loss_pm)
 // ---- streamed model: Alg. 3's three operations on a block ----
 int stream_prefetch(zo_model *m, int block)
 {
-    const int slot = block & 1;
+    if (m->blk_dev[block]) return ZO_OK;                  // lives in HBM: nothing to upload
+    const int slot = m->blk_slot[block];
     if (m->slot_state[slot] == SLOT_UPLOADED)
         return fail(ZO_ESTATE, "slot %d still holds block %d awaiting COMPUTE", slot, m->slot_block[slot]);
     if (m->slot_state[slot] == SLOT_COMPUTED && m->slot_dirty[slot])
@@ -482,7 +489,18 @@ int stream_prefetch(zo_model *m, int block)
 // wait for the upload, apply the updates the host copy lacks, optionally stage + forward
 int stream_compute(zo_model *m, int block, bool forward, bool force_writeback = false)
 {
-    const int slot = block & 1;
+    if (m->blk_dev[block]) {
+        // a block that stays in HBM is visited once per step and only ever lacks the newest update (Alg. 2: a
+        // module takes last step's update at its visit)
+        if (m->pend_n > 0)
+            ZO_TRY(axpy_range(m, 2 + kPerBlock * block, kPerBlock, m->pend_seed[m->pend_n - 1], 0.0f, m->s_pend + (m->pend_n - 1), true));
+        if (forward) {
+            ZO_TRY(stage_block(m, block, nullptr, m->step_seed, m->step_eps, false));
+            ZO_TRY(block_forward(m, 2, m->step_batch, m->step_seq));
+        }
+        return ZO_OK;
+    }
+    const int slot = m->blk_slot[block];
     if (m->slot_state[slot] != SLOT_UPLOADED || m->slot_block[slot] != block)
         return fail(ZO_ESTATE, "block %d was not prefetched", block);
     ZO_HIP(hipStreamWaitEvent(m->compute, m->ev_uploaded[slot], 0));
@@ -513,7 +531,8 @@ int stream_compute(zo_model *m, int block, bool forward, bool force_writeback = 
 
 int stream_writeback(zo_model *m, int block)
 {
-    const int slot = block & 1;
+    if (m->blk_dev[block]) return ZO_OK;
+    const int slot = m->blk_slot[block];
     if (m->slot_state[slot] != SLOT_COMPUTED || m->slot_block[slot] != block)
         return fail(ZO_ESTATE, "block %d is not computed in slot %d", block, slot);
     if (m->slot_dirty[slot]) {
@@ -522,6 +541,21 @@ int stream_writeback(zo_model *m, int block)
         ZO_HIP(hipMemcpyAsync(m->tptr[2 + kPerBlock * block], m->ws + m->wsp.slot[slot], bytes, hipMemcpyDeviceToHost, m->download));
         ZO_HIP(hipEventRecord(m->ev_written[slot], m->download));
         m->slot_dirty[slot] = false;
+    }
+    return ZO_OK;
+}
+
+// Enqueue the uploads of the next host blocks for as long as a slot is free for them (one is while its previous
+// occupant has been computed and, if it was updated, written back).  With two slots the upload of the block after
+// next starts as soon as the one before it has been staged, whatever number of HBM-resident blocks lie in between.
+int stream_fill(zo_model *m)
+{
+    for (int b = m->up_next; b < m->cfg.n_layers; ++b) {
+        if (m->blk_dev[b]) continue;
+        const int slot = m->blk_slot[b];
+        if (m->slot_state[slot] == SLOT_UPLOADED || (m->slot_state[slot] == SLOT_COMPUTED && m->slot_dirty[slot])) break;
+        ZO_TRY(stream_prefetch(m, b));
+        m->up_next = b + 1;
     }
     return ZO_OK;
 }
@@ -595,13 +629,34 @@ extern "C" int zo_init_model(const zo_config *cfg, void *const *tensor_ptrs, int
     m->compute = (hipStream_t)compute_stream; m->upload = (hipStream_t)copy_stream; m->download = nullptr; m->own_download = false;
     m->use_mfma = true;
     const size_t e = elem_bytes(cfg->dtype);
+    m->blk_dev.assign(cfg->n_layers, cfg->residency == ZO_STREAMED ? 0 : 1);
+    m->blk_slot.assign(cfg->n_layers, 0);
+    m->up_next = 0;
     if (cfg->residency == ZO_STREAMED) {
-        for (int l = 0; l < cfg->n_layers; ++l)
+        int n_host = 0;
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            int n_dev = 0;
+            for (int k = 0; k < kPerBlock; ++k) {
+                hipPointerAttribute_t attr;
+                if (hipPointerGetAttributes(&attr, m->tptr[2 + kPerBlock * l + k]) != hipSuccess) {
+                    (void)hipGetLastError();                      // plain host memory on runtimes that report it as an error
+                    continue;
+                }
+                if (attr.type == hipMemoryTypeDevice) ++n_dev;
+            }
+            if (n_dev != 0 && n_dev != kPerBlock) {
+                delete m;
+                return fail(ZO_EINVAL, "streamed model: block %d lies partly in device and partly in host memory", l);
+            }
+            m->blk_dev[l] = n_dev == kPerBlock;
+            if (m->blk_dev[l]) continue;
+            m->blk_slot[l] = n_host++ & 1;
             for (int k = 1; k < kPerBlock; ++k)
                 if ((char *)m->tptr[2 + kPerBlock * l + k] != (char *)m->tptr[2 + kPerBlock * l] + m->lay.src_off[k] * e) {
                     delete m;
                     return fail(ZO_EINVAL, "streamed model: tensors of block %d are not adjacent in canonical order", l);
                 }
+        }
     }
     // descriptor table for the in-place passes; streamed block tensors are addressed in their device slot
     m->descs.resize(n_tensors);
@@ -609,9 +664,9 @@ extern "C" int zo_init_model(const zo_config *cfg, void *const *tensor_ptrs, int
     for (int t = 0; t < n_tensors; ++t) {
         TensorDesc &d = m->descs[t];
         void *p = m->tptr[t];
-        if (cfg->residency == ZO_STREAMED && is_block_tensor(m, t)) {
+        if (is_block_tensor(m, t) && !m->blk_dev[(t - 2) / kPerBlock]) {
             const int l = (t - 2) / kPerBlock, k = (t - 2) % kPerBlock;
-            p = m->ws + wsp.slot[l & 1] + m->lay.src_off[k] * e;
+            p = m->ws + wsp.slot[m->blk_slot[l]] + m->lay.src_off[k] * e;
         }
         d.src = p; d.dst = p; d.numel = tensor_numel(*cfg, m->lay, t); d.first_chunk = chunk; d.tid = (uint32_t)t; d.pad = 0;
         chunk += (d.numel + kAxpyChunk - 1) / kAxpyChunk;
@@ -684,7 +739,8 @@ extern "C" int zo_perturb(zo_model *m, uint64_t seed, float scale, int first_ten
         return fail(ZO_EINVAL, "tensor range [%d, %d) outside [0, %d)", first_tensor, first_tensor + n_tensors, m->n_tensors);
     if (m->cfg.residency == ZO_STREAMED)
         for (int t = first_tensor; t < first_tensor + n_tensors; ++t)
-            if (is_block_tensor(m, t)) return fail(ZO_ESTATE, "tensor %d lives in host memory; use the streamed step", t);
+            if (is_block_tensor(m, t) && !m->blk_dev[(t - 2) / kPerBlock])
+                return fail(ZO_ESTATE, "tensor %d lives in host memory; use the streamed step", t);
     ZO_TRY(apply_pending_resident(m));
     return axpy_range(m, first_tensor, n_tensors, seed, scale, nullptr);
 }
@@ -737,12 +793,13 @@ extern "C" int zo_step(zo_model *m, const int32_t *tokens, int batch, int seq, u
     if (mode != ZO_MODE_FUSED) return fail(ZO_EINVAL, "a streamed model supports ZO_MODE_FUSED only");
     // Alg. 3: U(W_{i+1}) is in flight while C(W_i) runs; O(W_i) follows as soon as W_i is staged.
     ZO_TRY(stream_begin(m, tokens, batch, seq, seed, eps));
-    ZO_TRY(stream_prefetch(m, 0));
+    m->up_next = 0;
+    ZO_TRY(stream_fill(m));
     for (int l = 0; l < m->cfg.n_layers; ++l) {
-        if (l + 1 < m->cfg.n_layers) ZO_TRY(stream_prefetch(m, l + 1));
         ZO_TRY(stream_compute(m, l, true));
         m->next_block = l + 1;
         ZO_TRY(stream_writeback(m, l));
+        ZO_TRY(stream_fill(m));
     }
     ZO_TRY(stream_end(m, lr));
     return read_back(m, host_g, host_loss_pm);
@@ -823,11 +880,12 @@ extern "C" int zo_flush_pending(zo_model *m)
         ZO_TRY(axpy_range(m, lnf, 2, m->pend_seed[m->pend_n - 1], 0.0f, m->s_pend + (m->pend_n - 1), true));
         m->resident_pending = false;
     }
-    ZO_TRY(stream_prefetch(m, 0));
+    m->up_next = 0;
+    ZO_TRY(stream_fill(m));
     for (int l = 0; l < m->cfg.n_layers; ++l) {
-        if (l + 1 < m->cfg.n_layers) ZO_TRY(stream_prefetch(m, l + 1));
         ZO_TRY(stream_compute(m, l, false, true));
         ZO_TRY(stream_writeback(m, l));
+        ZO_TRY(stream_fill(m));
     }
     ZO_HIP(hipStreamSynchronize(m->download));
     ZO_HIP(hipStreamSynchronize(m->compute));

@@ -42,10 +42,11 @@ def resid_dtype(dtype):
 
 
 class Model:
-    """A resident or streamed model over seeded synthetic weights."""
+    """A resident or streamed model over seeded synthetic weights.  `device_blocks`: blocks of a streamed model
+    that are kept in device memory instead of pinned host memory."""
 
     def __init__(self, n_layers, d_model, n_heads, d_ffn, vocab, max_pos, dtype, batch, seq, seed=0, plain_small=False,
-                 std=0.02, streamed=False):
+                 std=0.02, streamed=False, device_blocks=()):
         self.dtype, self.batch, self.seq = dtype, batch, seq
         self.ocfg = zo.Config(n_layers, d_model, n_heads, d_ffn, vocab, max_pos, dtype)
         self.theta0 = zi.make_weights(self.ocfg.shapes(), dtype, seed=seed, std=std, plain_small=plain_small)
@@ -64,7 +65,7 @@ class Model:
             self.tensors, ptrs = [], []
             esz = self.host_blocks.element_size()
             for i, t in enumerate(self.theta0):
-                if 2 <= i < 2 + 16 * n_layers:
+                if 2 <= i < 2 + 16 * n_layers and (i - 2) // 16 not in device_blocks:
                     l, k = divmod(i - 2, 16)
                     off = sum(int(np.prod(s)) for _, s in self.ocfg.shapes()[2:2 + k])
                     view = self.host_blocks[l, off:off + t.size]

@@ -144,3 +144,45 @@ def test_writeback_interval_leaves_results_bit_identical(dtype, interval):
     zo_amd.zo_flush_pending(stm.handle)
     assert all(x.tobytes() == y.tobytes() for x, y in zip(res.theta(), stm.theta()))
     res.close(); stm.close()
+
+
+@pytest.mark.parametrize("dtype,device_blocks,interval", [(zi.BF16, (0,), 1), (zi.BF16, (1,), 1), (zi.BF16, (0, 2), 3),
+                                                         (zi.FP16, (1, 2), 2), (zi.FP32, (0, 1, 2), 1), (zi.BF16, (2,), 2)])
+def test_blocks_kept_in_hbm_leave_results_bit_identical(dtype, device_blocks, interval):
+    """A streamed model keeps each block where its pointers say: some in pinned host memory (uploaded per visit),
+    some in device memory (no transfer).  Losses, g and, after a flush, theta are those of the resident model bit
+    for bit, for any placement, with the write-back interval and the stochastic rounding as well."""
+    lr = {zi.BF16: 3e-2, zi.FP16: 3e-3, zi.FP32: 1e-3}[dtype]
+    kw = dict(dtype=dtype, batch=2, seq=40, seed=3, plain_small=False, std=0.05)
+    res = Model(**SHAPE, **kw)
+    mix = Model(**SHAPE, streamed=True, device_blocks=device_blocks, **kw)
+    if interval > 1:
+        zo_amd.zo_set_writeback_interval(mix.handle, interval)
+    if dtype == zi.FP16:
+        for mdl in (res, mix):
+            zo_amd.zo_set_update_rounding(mdl.handle, zo_amd.ZO_ROUND_STOCHASTIC)
+    tok, tok_dev = res.tokens()
+    for seed in range(2 * interval + 1):
+        a = zo_amd.zo_step(res.handle, tok_dev, 2, 40, seed, 1e-3, lr)
+        b = zo_amd.zo_step(mix.handle, tok_dev, 2, 40, seed, 1e-3, lr)
+        assert a == b, (seed, a, b)
+    assert any(x.tobytes() != y.tobytes() for x, y in zip(res.theta(), mix.theta()))      # the last update is pending
+    zo_amd.zo_flush_pending(mix.handle)
+    assert all(x.tobytes() == y.tobytes() for x, y in zip(res.theta(), mix.theta()))
+    # and on after the flush, through the manual schedule (uploads and write-backs of HBM blocks are no-ops)
+    zo_amd.zo_stream_begin(mix.handle, tok_dev, 2, 40, 77, 1e-3)
+    P, C, W = zo_amd.ZO_PHASE_PREFETCH, zo_amd.ZO_PHASE_COMPUTE, zo_amd.ZO_PHASE_WRITEBACK
+    for l in range(SHAPE["n_layers"]):
+        zo_amd.zo_stream_block(mix.handle, l, P | C | W)
+    b = zo_amd.zo_stream_end(mix.handle, lr)
+    a = zo_amd.zo_step(res.handle, tok_dev, 2, 40, 77, 1e-3, lr)
+    assert a == b
+    zo_amd.zo_flush_pending(mix.handle)
+    assert all(x.tobytes() == y.tobytes() for x, y in zip(res.theta(), mix.theta()))
+    # a perturbation may touch a block in HBM, not one in host memory
+    zo_amd.zo_perturb(mix.handle, 5, 1e-3, 2 + 16 * device_blocks[0], 16)
+    host_blocks = [l for l in range(SHAPE["n_layers"]) if l not in device_blocks]
+    if host_blocks:
+        with pytest.raises(zo_amd.ZoError):
+            zo_amd.zo_perturb(mix.handle, 5, 1e-3, 2 + 16 * host_blocks[0], 16)
+    res.close(); mix.close()
