@@ -352,13 +352,16 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
                 gload_lds16(gbase, offs[q], st + q * 1024u);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            // back and forth over the activation fragments, so that one operand changes from one multiply to
+            // the next, not both (a little less switching on a chip whose clock is set by its power)
+            const int xi = ((j >> 2) & 1) ? 3 - (j & 3) : (j & 3);
             if (first) {
                 f32x16 zero;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
-                acc[j >> 2][j & 3] = mfma32<DT>(wf[j >> 2], xf[j & 3], zero);
+                acc[j >> 2][xi] = mfma32<DT>(wf[j >> 2], xf[xi], zero);
             } else {
-                acc[j >> 2][j & 3] = mfma32<DT>(wf[j >> 2], xf[j & 3], acc[j >> 2][j & 3]);
+                acc[j >> 2][xi] = mfma32<DT>(wf[j >> 2], xf[xi], acc[j >> 2][xi]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
