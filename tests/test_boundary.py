@@ -57,4 +57,10 @@ def test_host_side_argument_checks():
         zo_amd.zo_set_update_rounding(None, zo_amd.ZO_ROUND_STOCHASTIC)
     with pytest.raises(zo_amd.ZoError):
         zo_amd.zo_kernel_stage_pm(4096, 4096, 4096, 0, 8, 6, 1, 1, 0, 1e-3)     # transposed, cols % 4 != 0
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_kernel_stage_update_pm(4096, 4096, 4096, zo_amd.ZO_BF16, 8, 8, 0, 1, 0, 1e-3, 2, None)     # no step scalar
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_kernel_stage_update_pm(4096, 4096, 4096, zo_amd.ZO_FP32, 8, 8, 0, 1, 0, 1e-3, 2, 4096, True)   # fp32 + stochastic
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_set_deferred_update(None, 1)
     assert zo_amd.zo_free(None) is None
