@@ -242,6 +242,14 @@ int zo_kernel_stage_update_pm(void *theta, void *w_plus, void *w_minus, int dtyp
                               uint64_t seed, uint32_t tensor_id, float eps, uint64_t upd_seed,
                               const float *dev_scale, int stochastic, void *stream);
 
+/* Diagnostic, not a step of the path: the rate at which this chip issues 32x32x16 matrix multiplies of `dtype`
+ * (ZO_BF16 / ZO_FP16) when nothing else happens: no loads, 16 independent accumulators per wave, 4 waves per
+ * workgroup.  One launch does n_workgroups * 4 * iters * 16 multiplies of 2*32*32*16 FLOP.  With random_operands
+ * zero every operand is 0.0; otherwise the operands have random sign and mantissa, which is what a GEMM on real
+ * data feeds the pipe, and the clock the chip holds under its power limit is lower.  out: device, at least
+ * n_workgroups * 256 floats (each thread writes one sum, so the work cannot be elided). */
+int zo_probe_mfma_rate(float *out, int dtype, int n_workgroups, int iters, int random_operands, void *stream);
+
 /* Sign-batched linear layer:  rows [0, m_half) of x use (wt_plus, b_plus), rows
  * [m_half, 2 m_half) use (wt_minus, b_minus):  y = x W + b with W given transposed as
  * wt[n, k].  x is [2 m_half, k].  2-byte dtypes run on MFMA with fp32 accumulation;

@@ -25,6 +25,7 @@ EXPORTS = (
     "zo_last_error", "zo_profile_begin", "zo_profile_end",
     "zo_kernel_z", "zo_kernel_normal_pairs", "zo_kernel_axpy_z", "zo_kernel_axpy_z_sr", "zo_kernel_stage_pm", "zo_kernel_stage_update_pm", "zo_kernel_linear_pm",
     "zo_kernel_layernorm_pm", "zo_kernel_attention", "zo_kernel_lmhead_scratch_bytes", "zo_kernel_lmhead_ce",
+    "zo_probe_mfma_rate",
 )
 
 
@@ -78,6 +79,7 @@ def lib():
         L.zo_kernel_axpy_z_sr.argtypes = [vp, vp, i32, u64, u64, u32, f32, vp, vp]
         L.zo_kernel_stage_pm.argtypes = [vp, vp, vp, i32, i32, i32, i32, u64, u32, f32, vp]
         L.zo_kernel_stage_update_pm.argtypes = [vp, vp, vp, i32, i32, i32, i32, u64, u32, f32, u64, vp, i32, vp]
+        L.zo_probe_mfma_rate.argtypes = [vp, i32, i32, i32, i32, vp]
         L.zo_kernel_linear_pm.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.zo_kernel_layernorm_pm.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]
         L.zo_kernel_attention.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
@@ -235,6 +237,10 @@ def zo_kernel_stage_update_pm(theta, w_plus, w_minus, dtype, rows, cols, transpo
                               stochastic=False, stream=None):
     _check(lib().zo_kernel_stage_update_pm(_ptr(theta), _ptr(w_plus), _ptr(w_minus), dtype, rows, cols, int(transpose), seed,
                                            tensor_id, eps, upd_seed, _ptr(dev_scale), int(stochastic), _stream(stream)))
+
+
+def zo_probe_mfma_rate(out, dtype, n_workgroups, iters, random_operands=True, stream=None):
+    _check(lib().zo_probe_mfma_rate(_ptr(out), dtype, n_workgroups, iters, int(random_operands), _stream(stream)))
 
 
 def zo_kernel_linear_pm(x, wt_plus, wt_minus, b_plus, b_minus, y, dtype, m_half, n, k, epilogue, stream=None):

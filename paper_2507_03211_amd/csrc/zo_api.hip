@@ -1004,6 +1004,16 @@ extern "C" int zo_kernel_stage_update_pm(void *theta, void *w_plus, void *w_minu
     return ZO_OK;
 }
 
+extern "C" int zo_probe_mfma_rate(float *out, int dtype, int n_workgroups, int iters, int random_operands, void *stream)
+{
+    ZO_TRY(check_dtype(dtype));
+    if (dtype == ZO_FP32) return fail(ZO_EINVAL, "the probe issues 16-bit multiplies: ZO_BF16 or ZO_FP16");
+    if (!out) return fail(ZO_EINVAL, "NULL argument");
+    if (n_workgroups < 1 || n_workgroups > (1 << 20) || iters < 1) return fail(ZO_EINVAL, "bad launch shape");
+    ZO_HIP(launch_mfma_probe(out, dtype, n_workgroups, iters, random_operands != 0, (hipStream_t)stream));
+    return ZO_OK;
+}
+
 extern "C" int zo_kernel_linear_pm(const void *x, const void *wt_plus, const void *wt_minus, const void *b_plus, const void *b_minus,
                                    void *y, int dtype, int m_half, int n, int k, int epilogue, void *stream)
 {

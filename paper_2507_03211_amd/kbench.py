@@ -4,6 +4,11 @@
     python -m paper_2507_03211_amd.kbench attention --n-seq 8 --seq 2048 --heads 40 --d-head 128
     python -m paper_2507_03211_amd.kbench axpy --n 314572800 --dtype bf16
     python -m paper_2507_03211_amd.kbench stage --rows 5120 --cols 20480 --transpose 1
+    python -m paper_2507_03211_amd.kbench mfma-rate --dtype bf16
+
+`mfma-rate` is no kernel of the path: it issues nothing but matrix multiplies, once on zeros and once on operands of
+random sign and mantissa, and prints both rates: the second is what the chip sustains under its power limit and is
+the ceiling the GEMM's fraction of the nominal peak has to be read against.
 
 Prints one JSON line per run: milliseconds per launch (HIP events on the launch stream) and the
 achieved rate against the roofline that bounds the kernel (bf16/fp16 MFMA 2.5 PFLOP/s, HBM 8 TB/s).
@@ -34,7 +39,7 @@ def timed(fn, reps, warm=2):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("kernel", choices=["linear", "attention", "axpy", "stage", "layernorm"])
+    ap.add_argument("kernel", choices=["linear", "attention", "axpy", "stage", "layernorm", "mfma-rate"])
     ap.add_argument("--dtype", default="bf16", choices=list(DT))
     ap.add_argument("--reps", type=int, default=10)
     ap.add_argument("--m-half", type=int, default=8192)
@@ -48,6 +53,8 @@ def main():
     ap.add_argument("--rows", type=int, default=5120)
     ap.add_argument("--cols", type=int, default=5120)
     ap.add_argument("--transpose", type=int, default=1)
+    ap.add_argument("--workgroups", type=int, default=1024, help="mfma-rate: workgroups of 4 waves")
+    ap.add_argument("--iters", type=int, default=20000, help="mfma-rate: 16 multiplies per wave and iteration")
     ap.add_argument("--stochastic", action="store_true", help="axpy: the stochastically rounded update (16-bit types)")
     a = ap.parse_args()
     code, tdt = DT[a.dtype]
@@ -86,6 +93,15 @@ def main():
         gb = 3.0 * a.rows * a.cols * esz / 1e9
         out.update(shape=[a.rows, a.cols], transpose=a.transpose, ms=ms, gbs=gb / (ms * 1e-3), frac_of_hbm=gb / (ms * 1e-3) / 8000.0,
                    gelem_per_s=a.rows * a.cols / ms / 1e6)
+    elif a.kernel == "mfma-rate":
+        if code == zo.ZO_FP32:
+            raise SystemExit("mfma-rate issues 16-bit multiplies: --dtype bf16 or f16")
+        sink = torch.empty(a.workgroups * 256, device=dev, dtype=torch.float32)
+        flops = a.workgroups * 4.0 * a.iters * 16 * 2 * 32 * 32 * 16
+        out.update(workgroups=a.workgroups, iters=a.iters)
+        for name, rnd in (("zero_operands", False), ("random_operands", True)):
+            ms = timed(lambda: zo.zo_probe_mfma_rate(sink, code, a.workgroups, a.iters, rnd), a.reps)
+            out[name] = {"ms": ms, "tflops": flops / ms / 1e9, "frac_of_peak": flops / ms / 1e9 / 2500.0}
     else:
         rdt = torch.float64 if code == zo.ZO_FP32 else torch.float32
         adt = torch.float64 if code == zo.ZO_FP32 else tdt

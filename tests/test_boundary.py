@@ -63,4 +63,10 @@ def test_host_side_argument_checks():
         zo_amd.zo_kernel_stage_update_pm(4096, 4096, 4096, zo_amd.ZO_FP32, 8, 8, 0, 1, 0, 1e-3, 2, 4096, True)   # fp32 + stochastic
     with pytest.raises(zo_amd.ZoError):
         zo_amd.zo_set_deferred_update(None, 1)
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_probe_mfma_rate(4096, zo_amd.ZO_FP32, 8, 8)       # the probe has no fp32 form
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_probe_mfma_rate(None, zo_amd.ZO_BF16, 8, 8)
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_probe_mfma_rate(4096, zo_amd.ZO_BF16, 0, 8)
     assert zo_amd.zo_free(None) is None

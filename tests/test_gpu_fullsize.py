@@ -182,3 +182,18 @@ def test_step_invariants_at_opt_1_3b_size():
     assert after != a
     assert zo_amd.zo_device_flags(h) == 0
     zo_amd.zo_free(h)
+
+
+@pytest.mark.parametrize("dtype", [zo_amd.ZO_BF16, zo_amd.ZO_FP16])
+def test_matrix_rate_probe_runs_its_multiplies(dtype):
+    """The diagnostic that measures the matrix-instruction rate: every thread writes its sum, zeros stay zero,
+    random operands give the same finite non-zero sums on every launch."""
+    wgs, iters = 16, 3
+    sink = torch.full((wgs * 256,), 7.0, device=DEV)
+    zo_amd.zo_probe_mfma_rate(sink, dtype, wgs, iters, False)
+    assert torch.count_nonzero(sink).item() == 0
+    zo_amd.zo_probe_mfma_rate(sink, dtype, wgs, iters, True)
+    a = sink.clone()
+    zo_amd.zo_probe_mfma_rate(sink, dtype, wgs, iters, True)
+    assert torch.isfinite(a).all() and torch.count_nonzero(a).item() > a.numel() // 2
+    assert torch.equal(a, sink)
