@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--transpose", type=int, default=1)
     ap.add_argument("--workgroups", type=int, default=1024, help="mfma-rate: workgroups of 4 waves")
     ap.add_argument("--iters", type=int, default=20000, help="mfma-rate: 16 multiplies per wave and iteration")
+    ap.add_argument("--operands", default="random", choices=["random", "zero"],
+                    help="linear: all-zero operands take the chip's power limit out of the timing (what is left is the kernel's own stalls)")
     ap.add_argument("--stochastic", action="store_true", help="axpy: the stochastically rounded update (16-bit types)")
     a = ap.parse_args()
     code, tdt = DT[a.dtype]
@@ -63,14 +65,15 @@ def main():
     out = {"kernel": a.kernel, "dtype": a.dtype}
     if a.kernel == "linear":
         act = torch.float64 if code == zo.ZO_FP32 else tdt
-        x = torch.randn(2 * a.m_half, a.k, device=dev).to(act)
-        w = [(0.02 * torch.randn(a.n, a.k, device=dev)).to(tdt) for _ in range(2)]
+        scale = 0.0 if a.operands == "zero" else 1.0
+        x = (scale * torch.randn(2 * a.m_half, a.k, device=dev)).to(act)
+        w = [(0.02 * scale * torch.randn(a.n, a.k, device=dev)).to(tdt) for _ in range(2)]
         b = [torch.zeros(a.n, device=dev, dtype=tdt) for _ in range(2)]
         ydt = act if a.epilogue in (0, 1) else (torch.float64 if code == zo.ZO_FP32 else torch.float32)
         y = torch.zeros(2 * a.m_half, a.n, device=dev, dtype=ydt)
         ms = timed(lambda: zo.zo_kernel_linear_pm(x, w[0], w[1], b[0], b[1], y, code, a.m_half, a.n, a.k, a.epilogue), a.reps)
         flops = 2.0 * 2 * a.m_half * a.n * a.k
-        out.update(shape=[2 * a.m_half, a.n, a.k], epilogue=a.epilogue, ms=ms, tflops=flops / ms / 1e9,
+        out.update(shape=[2 * a.m_half, a.n, a.k], epilogue=a.epilogue, operands=a.operands, ms=ms, tflops=flops / ms / 1e9,
                    frac_of_peak=flops / ms / 1e9 / 2500.0)
     elif a.kernel == "attention":
         d = a.heads * a.d_head
