@@ -126,7 +126,9 @@ int zo_dual_forward(zo_model *m, const int32_t *tokens, int batch, int seq, uint
  * blocks are uploaded one ahead of the computation, each block's update from the previous
  * step is applied right after its upload and written back, and this step's update stays
  * pending until the next zo_step or zo_flush_pending.
- *   host_g, host_loss_pm   host, double[1] / double[2], nullable; non-NULL synchronises. */
+ *   host_g, host_loss_pm   host, double[1] / double[2], nullable; non-NULL synchronises.
+ * A ZO_STREAMED step always returns with its kernels finished (its last write-backs may still be running): the
+ * schedule of Alg. 3 only holds on the device if the host does not queue steps ahead of it. */
 int zo_step(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t seed,
             float eps, float lr, int mode, double *host_g, double *host_loss_pm);
 
