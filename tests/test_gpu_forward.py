@@ -228,3 +228,24 @@ def test_small_low_precision_model_matches_oracle(dtype):
     assert abs(lp / olp - 1) < tol and abs(lm / olm - 1) < tol
     assert all(a.tobytes() == b.tobytes() for a, b in zip(mdl.theta(), mdl.theta0))      # fused mode never writes theta
     mdl.close()
+
+
+@pytest.mark.parametrize("dtype", [zi.FP32, zi.BF16])
+def test_degenerate_shapes_match_oracle(dtype):
+    """The smallest step there is: one block, one head, one sequence of two tokens (a single predicted token),
+    then a call with fewer tokens than the model was set up for (batch 1 x seq 2 inside 3 x 9)."""
+    for alloc, call in (((1, 2), (1, 2)), ((3, 9), (1, 2)), ((3, 9), (3, 9))):
+        mdl = Model(1, 64, 1, 128, 96, 16, dtype, alloc[0], alloc[1], plain_small=False, std=0.05)
+        tok, tok_dev = mdl.tokens(batch=call[0], seq=call[1])
+        theta = [t.copy() for t in mdl.theta0]
+        lp, lm, g = zo_amd.zo_step(mdl.handle, tok_dev, call[0], call[1], 11, 1e-3, 1e-4)
+        olp, olm, og = zo.zo_step_fused(mdl.ocfg, theta, tok, 11, 1e-3, 1e-4)
+        tol = 1e-10 if dtype == zi.FP32 else 2e-2
+        assert abs(lp / olp - 1) < tol and abs(lm / olm - 1) < tol, (alloc, call, lp, olp)
+        if dtype == zi.FP32:
+            assert abs(g / og - 1) < 1e-5, (alloc, call, g, og)
+        # the update is the kernel's own g times the oracle's z: bit-exact given that scalar
+        want = [zo.axpy_z(t, mdl.dtype, 11, i, zo.step_scalar(1e-4, g)) for i, t in enumerate(mdl.theta0)]
+        assert all(a.tobytes() == b.tobytes() for a, b in zip(mdl.theta(), want)), (alloc, call)
+        assert zo_amd.zo_device_flags(mdl.handle) == 0
+        mdl.close()
