@@ -32,7 +32,7 @@ def _weights(rng, shape, dtype, std=0.05):
 
 
 @pytest.mark.parametrize("dtype", [zi.FP32, zi.BF16, zi.FP16])
-@pytest.mark.parametrize("m_half,d", [(5, 64), (33, 768), (64, 200)])
+@pytest.mark.parametrize("m_half,d", [(5, 64), (33, 768), (64, 200), (7, 2048), (6, 2052), (4, 5120), (3, 12288), (9, 6000), (5, 12292)])
 def test_layernorm(dtype, m_half, d):
     rng = np.random.Generator(np.random.PCG64(d))
     h = rng.standard_normal((2 * m_half, d)) * 3 + 0.5
