@@ -73,8 +73,9 @@ __device__ __forceinline__ float sqrt_rn(float t)
 __device__ __forceinline__ void normal_pair(uint32_t ra, uint32_t rb, float &z0, float &z1)
 {
     // radius^2 = -2 ln u, with u = m 2^e and m in [sqrt(1/2), sqrt(2))
-    const float u = (float)(2u * (ra >> 9) + 1u) * 0x1p-24f;
-    const uint32_t ix = __float_as_uint(u) - 0x3f3504f3u;
+    // (the factor 2^-24 is taken off the exponent field instead of multiplied in: 24 << 23 = 0x0c000000)
+    const float u24 = (float)(2u * (ra >> 9) + 1u);
+    const uint32_t ix = __float_as_uint(u24) - (0x3f3504f3u + 0x0c000000u);
     const float ef = (float)((int32_t)ix >> 23);
     const float m = __uint_as_float((ix & 0x007fffffu) + 0x3f3504f3u);
     const float r = m - 1.0f;
