@@ -79,19 +79,21 @@ __device__ __forceinline__ void normal_pair(uint32_t ra, uint32_t rb, float &z0,
     const float ef = (float)((int32_t)ix >> 23);
     const float m = __uint_as_float((ix & 0x007fffffu) + 0x3f3504f3u);
     const float r = m - 1.0f;
-    float q = -0x1.38b2a8p-4f;                       // ln(1+r) = r - r^2/2 + r^3 q(r)
-    q = __builtin_fmaf(q, r, 0x1.055ad8p-3f);
-    q = __builtin_fmaf(q, r, -0x1.0d8586p-3f);
-    q = __builtin_fmaf(q, r, 0x1.22da36p-3f);
-    q = __builtin_fmaf(q, r, -0x1.547240p-3f);
-    q = __builtin_fmaf(q, r, 0x1.99a008p-3f);
-    q = __builtin_fmaf(q, r, -0x1.000228p-2f);
-    q = __builtin_fmaf(q, r, 0x1.555554p-2f);
+    // The radius needs t = -2 ln u.  The factor -2 is carried through the sum instead of multiplied in at the end:
+    // every coefficient below is -2 times that of ln(1+r) = r - r^2/2 + r^3 q(r), and a power of two scales
+    // every intermediate exactly, so t has the bits of -2 * (e ln 2 + ln m) evaluated step by step.
+    float q = 0x1.38b2a8p-3f;
+    q = __builtin_fmaf(q, r, -0x1.055ad8p-2f);
+    q = __builtin_fmaf(q, r, 0x1.0d8586p-2f);
+    q = __builtin_fmaf(q, r, -0x1.22da36p-2f);
+    q = __builtin_fmaf(q, r, 0x1.547240p-2f);
+    q = __builtin_fmaf(q, r, -0x1.99a008p-2f);
+    q = __builtin_fmaf(q, r, 0x1.000228p-1f);
+    q = __builtin_fmaf(q, r, -0x1.555554p-1f);
     const float r2 = r * r;
     const float r3 = r2 * r;
-    const float lnm = __builtin_fmaf(r3, q, __builtin_fmaf(-0.5f, r2, r));
-    const float lnu = __builtin_fmaf(ef, 0x1.62e430p-1f, lnm);
-    const float rho = sqrt_rn(-2.0f * lnu);
+    const float lnm = __builtin_fmaf(r3, q, __builtin_fmaf(-2.0f, r, r2));
+    const float rho = sqrt_rn(__builtin_fmaf(ef, -0x1.62e430p+0f, lnm));
 
     // quarter-turn fraction folded at its middle: polynomials see [0, 1/2]
     const uint32_t k = (rb >> 6) & 0xFFFFFFu;
