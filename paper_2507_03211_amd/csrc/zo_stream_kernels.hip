@@ -306,45 +306,46 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
     const uint32_t rb = threadIdx.x / 16, cb = threadIdx.x % 16;
     const uint32_t c = c0 + 4 * cb;
     W vp[4][4], vm[4][4];                           // [row in patch][column in patch]
+    // Rows or columns past the edge of the matrix are computed like the others, from element 0 (always there),
+    // and never leave LDS: one straight-line body for the four rows lets the compiler share the generator's
+    // constants between them instead of setting them up again behind every bounds branch.
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         const uint32_t r = r0 + 4 * rb + it;
-        if (r < d.rows && c < d.cols) {
-            const uint64_t i0 = (uint64_t)r * d.cols + c;
-            W raw[4];
-            if constexpr (sizeof(W) == 2) *(uint2 *)raw = *(const uint2 *)(src + i0);
-            else *(uint4 *)raw = *(const uint4 *)(src + i0);
-            if constexpr (SINGLE) {
+        const bool valid = r < d.rows && c < d.cols;
+        const uint64_t i0 = valid ? (uint64_t)r * d.cols + c : 0;
+        W raw[4];
+        if constexpr (sizeof(W) == 2) *(uint2 *)raw = *(const uint2 *)(src + i0);
+        else *(uint4 *)raw = *(const uint4 *)(src + i0);
+        if constexpr (SINGLE) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) vp[it][e] = raw[e];
-            } else {
-                float z[4];
-                normal4(philox_block(seed, d.tid, i0 / 4), z);
-                if constexpr (UPD != 0) {
-                    float zu[4];
-                    normal4(philox_block(upd_seed, d.tid, i0 / 4), zu);
-                    u32x4 r{};
-                    if constexpr (UPD == 2) r = philox_block(upd_seed, d.tid, i0 / 4, 3u);
-                    const uint32_t rw[4] = {r.x, r.y, r.z, r.w};
+            for (int e = 0; e < 4; ++e) vp[it][e] = raw[e];
+        } else {
+            float z[4];
+            normal4(philox_block(seed, d.tid, i0 / 4), z);
+            if constexpr (UPD != 0) {
+                float zu[4];
+                normal4(philox_block(upd_seed, d.tid, i0 / 4), zu);
+                u32x4 rr{};
+                if constexpr (UPD == 2) rr = philox_block(upd_seed, d.tid, i0 / 4, 3u);
+                const uint32_t rw[4] = {rr.x, rr.y, rr.z, rr.w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float v = __builtin_fmaf(us, zu[e], Prec<DT>::w2f(raw[e]));
-                        if constexpr (UPD == 2) raw[e] = DT == kBF16 ? sr_to_bf16(v, rw[e]) : sr_to_f16(v, rw[e]);
-                        else raw[e] = Prec<DT>::f2w(v);
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    const float v = __builtin_fmaf(us, zu[e], Prec<DT>::w2f(raw[e]));
+                    if constexpr (UPD == 2) raw[e] = DT == kBF16 ? sr_to_bf16(v, rw[e]) : sr_to_f16(v, rw[e]);
+                    else raw[e] = Prec<DT>::f2w(v);
+                }
+                if (valid) {
                     if constexpr (sizeof(W) == 2) *(uint2 *)(theta + i0) = *(const uint2 *)raw;
                     else *(uint4 *)(theta + i0) = *(const uint4 *)raw;
                 }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float th = Prec<DT>::w2f(raw[e]);
-                    vp[it][e] = Prec<DT>::f2w(__builtin_fmaf(eps, z[e], th));
-                    vm[it][e] = Prec<DT>::f2w(__builtin_fmaf(-eps, z[e], th));
-                }
             }
-        } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { vp[it][e] = W(0); vm[it][e] = W(0); }
+            for (int e = 0; e < 4; ++e) {
+                const float th = Prec<DT>::w2f(raw[e]);
+                vp[it][e] = Prec<DT>::f2w(__builtin_fmaf(eps, z[e], th));
+                vm[it][e] = Prec<DT>::f2w(__builtin_fmaf(-eps, z[e], th));
+            }
         }
     }
 #pragma unroll
