@@ -110,6 +110,33 @@ __global__ __launch_bounds__(256) void axpy_z_kernel(const TensorDesc *__restric
     const W *__restrict__ src = (const W *)d.src;
     W *__restrict__ dst = (W *)d.dst;
     constexpr int kIter = kAxpyChunk / (256 * VN);
+    if (base + kAxpyChunk <= d.numel) {
+        // a chunk that lies wholly inside its tensor (all but a tensor's last): no bounds logic between the
+        // iterations, so the compiler schedules them as one body and sets the generator's constants up once
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            const uint64_t i0 = base + (uint64_t)(it * 256 + threadIdx.x) * VN;
+            float z[VN];
+#pragma unroll
+            for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b);
+            float th[VN];
+            unpack16<DT>(*(const uint4 *)(src + i0), th);
+#pragma unroll
+            for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
+            if constexpr (SR) {
+                uint32_t rw[VN];
+#pragma unroll
+                for (int b = 0; b < VN / 4; ++b) {
+                    const u32x4 r = philox_block(seed, d.tid, i0 / 4 + b, 3u);
+                    rw[4 * b] = r.x; rw[4 * b + 1] = r.y; rw[4 * b + 2] = r.z; rw[4 * b + 3] = r.w;
+                }
+                *(uint4 *)(dst + i0) = pack16_sr<DT>(th, rw);
+            } else {
+                *(uint4 *)(dst + i0) = pack16<DT>(th);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int it = 0; it < kIter; ++it) {
         const uint64_t i0 = base + (uint64_t)(it * 256 + threadIdx.x) * VN;
