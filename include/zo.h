@@ -285,6 +285,26 @@ int zo_kernel_lmhead_ce(const void *x, const void *e_plus, const void *e_minus, 
                         double *row_loss, void *scratch, int dtype, int m_half, int d, int vocab,
                         void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): zo_kernel_lmhead_ce without the scratch argument.  The partial results
+ * live in a buffer that is part of the library, ZO_NOALLOC_SCRATCH_BYTES of device memory per GPU, held from
+ * the moment the library is loaded on that GPU until the process ends.  The call allocates and frees nothing,
+ * on the device or through any library; the first call on a device looks the buffer's address up once.
+ * Same arguments, results and errors as zo_kernel_lmhead_ce, and additionally
+ *   ZO_ENOMEM  the call's partial results do not fit ZO_NOALLOC_SCRATCH_BYTES (nothing is enqueued).  ZO_BF16 /
+ *              ZO_FP16 with d a multiple of 64: 2 m_half rows of P (max, sum-exp) pairs of 8 bytes plus 4 bytes,
+ *              P = 2 ceil(vocab / 256) when the 256-wide tiling runs (at least 128 tiles and d >= 192), else
+ *              2 ceil(vocab / 128): at vocab 50272 up to m_half = 5315, or 2666 with the 128-wide tiling.  Other
+ *              shapes and ZO_FP32 go through logits in row chunks that are cut to fit, and fail only when a
+ *              single row of vocab logits (4 bytes each, 8 for ZO_FP32) does not fit.
+ *   ZO_EHIP    the buffer's address cannot be obtained.
+ * All calls on one GPU share that GPU's buffer: calls whose kernels may overlap (different streams, or several
+ * host threads) race on it; serialise them.  The buffer keeps the previous call's contents; every word a call
+ * reads it has written first, so nothing needs clearing between calls. */
+#define ZO_NOALLOC_SCRATCH_BYTES (32u << 20)
+int zo_kernel_lmhead_ce_noalloc(const void *x, const void *e_plus, const void *e_minus, const int32_t *target,
+                                double *row_loss, int dtype, int m_half, int d, int vocab, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ EXPORTS = (
     "zo_last_error", "zo_profile_begin", "zo_profile_end",
     "zo_kernel_z", "zo_kernel_normal_pairs", "zo_kernel_axpy_z", "zo_kernel_axpy_z_sr", "zo_kernel_stage_pm", "zo_kernel_stage_update_pm", "zo_kernel_linear_pm",
     "zo_kernel_layernorm_pm", "zo_kernel_attention", "zo_kernel_lmhead_scratch_bytes", "zo_kernel_lmhead_ce",
-    "zo_probe_mfma_rate",
+    "zo_probe_mfma_rate", "zo_kernel_lmhead_ce_noalloc",
 )
 
 
@@ -86,6 +86,7 @@ def lib():
         L.zo_kernel_lmhead_scratch_bytes.restype = sz
         L.zo_kernel_lmhead_scratch_bytes.argtypes = [i32, i32, i32]
         L.zo_kernel_lmhead_ce.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
+        L.zo_kernel_lmhead_ce_noalloc.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
         _lib = L
     return _lib
 
@@ -264,3 +265,11 @@ def zo_kernel_lmhead_scratch_bytes(dtype, m_half, vocab):
 def zo_kernel_lmhead_ce(x, e_plus, e_minus, target, row_loss, scratch, dtype, m_half, d, vocab, stream=None):
     _check(lib().zo_kernel_lmhead_ce(_ptr(x), _ptr(e_plus), _ptr(e_minus), _ptr(target), _ptr(row_loss), _ptr(scratch),
                                      dtype, m_half, d, vocab, _stream(stream)))
+
+
+ZO_NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def zo_kernel_lmhead_ce_noalloc(x, e_plus, e_minus, target, row_loss, dtype, m_half, d, vocab, stream=None):
+    _check(lib().zo_kernel_lmhead_ce_noalloc(_ptr(x), _ptr(e_plus), _ptr(e_minus), _ptr(target), _ptr(row_loss),
+                                             dtype, m_half, d, vocab, _stream(stream)))

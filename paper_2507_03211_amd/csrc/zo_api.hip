@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1058,6 +1059,16 @@ extern "C" int zo_kernel_attention(const void *qkv, void *out, int dtype, int n_
 
 static int lmhead_rows(int m_half) { return m_half < 2048 ? m_half : 2048; }
 
+static int check_lmhead_args(const void *x, const void *e_plus, const void *e_minus, const int32_t *target, double *row_loss, int dtype,
+                             int m_half, int d, int vocab)
+{
+    ZO_TRY(check_dtype(dtype));
+    if (!x || !e_plus || !e_minus || !target || !row_loss) return fail(ZO_EINVAL, "NULL argument");
+    if (m_half < 1 || d < 1 || vocab < 2) return fail(ZO_EINVAL, "bad shape");
+    if (dtype != ZO_FP32 && (d % 8 || vocab % 8)) return fail(ZO_EINVAL, "d and vocab must be multiples of 8 for 2-byte types");
+    return ZO_OK;
+}
+
 extern "C" size_t zo_kernel_lmhead_scratch_bytes(int dtype, int m_half, int vocab)
 {
     if (dtype < 0 || dtype > 2 || m_half < 1 || vocab < 1) return 0;
@@ -1065,11 +1076,65 @@ extern "C" size_t zo_kernel_lmhead_scratch_bytes(int dtype, int m_half, int voca
 }
 
 extern "C" int zo_kernel_lmhead_ce(const void *x, const void *e_plus, const void *e_minus, const int32_t *target, double *row_loss,
-                                   void *scratch, int dtype, int m_half, int d, int vocab, void *stream)
+                                   void *scratch_mem, int dtype, int m_half, int d, int vocab, void *stream)
 {
-    ZO_TRY(check_dtype(dtype));
-    if (!x || !e_plus || !e_minus || !target || !row_loss || !scratch) return fail(ZO_EINVAL, "NULL argument");
-    if (m_half < 1 || d < 1 || vocab < 2) return fail(ZO_EINVAL, "bad shape");
-    if (dtype != ZO_FP32 && (d % 8 || vocab % 8)) return fail(ZO_EINVAL, "d and vocab must be multiples of 8 for 2-byte types");
-    return lmhead_ce(nullptr, (hipStream_t)stream, x, e_plus, e_minus, target, row_loss, scratch, lmhead_rows(m_half), dtype, 2, m_half, d, vocab, true);
+    ZO_TRY(check_lmhead_args(x, e_plus, e_minus, target, row_loss, dtype, m_half, d, vocab));
+    if (!scratch_mem) return fail(ZO_EINVAL, "NULL argument");
+    return lmhead_ce(nullptr, (hipStream_t)stream, x, e_plus, e_minus, target, row_loss, scratch_mem, lmhead_rows(m_half), dtype, 2, m_half, d, vocab, true);
+}
+
+// ------------------------------------------------------------------ the entry point that allocates nothing
+// The LM head's partial results (per-row, per-strip (max, sum-exp) pairs and target logits, or a chunk of logits)
+// in a buffer that belongs to the library instead of the caller: one array per GPU, created when the code object
+// is loaded on it and held until the process ends.  `scratch` is only the host-side name of that array; what
+// kernels and copies take is the device address hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) unsigned char scratch[ZO_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU, looked up once per device
+std::mutex g_scratch_mutex;
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    ZO_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ZO_EINVAL, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        ZO_HIP(hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(ZO_EHIP, "hipGetSymbolAddress gave no address for the scratch array on device %d", dev);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ZO_OK;
+}
+}  // namespace
+
+extern "C" int zo_kernel_lmhead_ce_noalloc(const void *x, const void *e_plus, const void *e_minus, const int32_t *target,
+                                           double *row_loss, int dtype, int m_half, int d, int vocab, void *stream)
+{
+    ZO_TRY(check_lmhead_args(x, e_plus, e_minus, target, row_loss, dtype, m_half, d, vocab));
+    // what this call's path really needs: the fused 16-bit head keeps (max, sum-exp) pairs and a target logit per row;
+    // the other path a chunk of logits, whose row count is cut down to what the buffer holds
+    const size_t cap = (size_t)ZO_NOALLOC_SCRATCH_BYTES, rows = 2 * (size_t)m_half;
+    int chunk_rows = lmhead_rows(m_half);
+    if (dtype != ZO_FP32 && mfma_linear_supported(m_half, vocab, d)) {
+        const size_t need = align_up(rows * (size_t)mfma_ce_partials(2, m_half, vocab, d) * 8) + rows * 4;
+        if (need > cap)
+            return fail(ZO_ENOMEM, "m_half %d x vocab %d needs %zu bytes of partial results, the built-in buffer holds %zu: use "
+                        "zo_kernel_lmhead_ce", m_half, vocab, need, cap);
+    } else {
+        const size_t per_row = (size_t)vocab * acc_bytes(dtype);
+        if (per_row > cap)
+            return fail(ZO_ENOMEM, "one row of %d logits needs %zu bytes, the built-in buffer holds %zu: use zo_kernel_lmhead_ce",
+                        vocab, per_row, cap);
+        if ((size_t)chunk_rows * per_row > cap) chunk_rows = (int)(cap / per_row);
+    }
+    void *buf = nullptr;
+    ZO_TRY(static_scratch(&buf));
+    // every byte of the buffer that a launch reads was written by an earlier kernel of the same call (the partials
+    // and target logits by the GEMM epilogue, the logits chunk by the GEMM): nothing has to start at zero
+    return lmhead_ce(nullptr, (hipStream_t)stream, x, e_plus, e_minus, target, row_loss, buf, chunk_rows, dtype, 2, m_half, d, vocab, true);
 }
