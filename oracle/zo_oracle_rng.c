@@ -20,7 +20,11 @@
  * 1, 2, 3", SC'11) followed by a pair-wise Box-Muller transform whose fp32
  * arithmetic is fixed operation by operation, so that "reset the seed" becomes
  * "use the same counters" and the bits can be reproduced on any IEEE-754
- * machine.
+ * machine.  The transform is laid out so that a GPU needs few instructions
+ * for it (a 512-entry pivot table takes the place of a long logarithm
+ * polynomial, the angle's sign bits take the place of quadrant logic); what
+ * it computes is the textbook sqrt(-2 ln u) (cos, sin)(angle), which is what
+ * the pins check it against.
  *
  * Precision: z is DEFINED in fp32 (this is part of the method's specification,
  * not an approximation of something else); the perturbation is one fp32 fused
@@ -76,65 +80,74 @@ static void block_for(uint64_t seed, uint32_t tensor_id, uint32_t stream_tag, ui
 static float u32_as_f32(uint32_t x) { float f; memcpy(&f, &x, 4); return f; }
 static uint32_t f32_as_u32(float f) { uint32_t x; memcpy(&x, &f, 4); return x; }
 
-/* Two standard normals from two 32-bit words (pair-wise Box-Muller).
- *   u     = (2*(ra>>9)+1) * 2^-24               in (0,1), exact in fp32
- *   q     = rb >> 30                            quadrant
- *   k     = (rb >> 6) & 0xFFFFFF                fraction of a quarter turn, f = k*2^-24
- *   rho   = sqrt(-2 ln u),  (z0, z1) = rho * (cos, sin)((q + f) * pi/2)
- * Every floating-point step is a single IEEE fp32 operation (mul, add, fma,
- * sqrt); fmaf() is the fused one. */
+/* Two standard normals from two 32-bit words (pair-wise Box-Muller):
+ *   u     = (2*(ra>>9)+1) * 2^-24                 in (0,1), 24 significant bits
+ *   rho   = sqrt(-2 ln u)
+ *   x     = (float)(int32_t)rb * 2^-31            in [-1, 1]: a quarter turn either way
+ *   z1    = rho * sin(pi x / 2)
+ *   z0    = +-rho * cos(pi x / 2), negative when bit 8 of ra is set
+ * ((cos, sin) of an angle uniform over the right half circle with an independent fair sign on the
+ * cosine is uniform over the circle.)  Every floating-point step is a single IEEE fp32 operation
+ * (conversion, mul, fma, sqrt), written out in the order the specification gives it.
+ *
+ * The logarithm.  uf = (float)(k * 2^8), k = 2*(ra>>9)+1, is exact; with E its biased exponent
+ * and lb = E & 1, u = m * 4^n where n = (E >> 1) - 79 is in -12..0 and m, the significand of uf
+ * under the exponent 126 + lb, is in [0.5, 2).  The 512 intervals of m selected by
+ * i = 256 lb + (top 8 fraction bits) each have a pivot p_i: the interval's midpoint,
+ *   p_i = (1 + (j + 1/2) / 256) * (lb ? 1 : 1/2),  j = i mod 256,
+ * except p_255 = 1 (the interval that ends at m = 1, where -2 ln u goes to zero and has to keep
+ * its relative accuracy).  With inv_i = fl(1 / p_i), taken from then on as the exact number it is,
+ * and l_i = fl(2 ln inv_i):
+ *   r = fma(m, inv_i, -1)                         |r| <= 2^-9, m = (1 + r) / inv_i exactly up to r's rounding
+ *   t = -2 ln u = n * (-4 ln 2) + l_i - 2 ln(1 + r)
+ * with -2 ln(1 + r) = r * (-2 + r * (1 + r * (-2/3))) + O(r^4). */
+static void ln_pivot(uint32_t i, float *inv, float *l)
+{
+    const double j = (double)(i & 255u), half = (i >> 8) ? 1.0 : 0.5;
+    const double p = i == 255u ? 1.0 : (1.0 + (j + 0.5) / 256.0) * half;
+    *inv = (float)(1.0 / p);
+    *l = (float)(2.0 * log((double)*inv));
+}
+
 void zo_oracle_normal_pair(uint32_t ra, uint32_t rb, float *z0, float *z1)
 {
     /* radius: t = -2 ln u */
-    float u = (float)(2u * (ra >> 9) + 1u) * 0x1p-24f;
-    uint32_t ix = f32_as_u32(u) - 0x3f3504f3u;          /* bits of sqrt(1/2) */
-    int32_t e = (int32_t)ix >> 23;                      /* u = m * 2^e, m in [sqrt(1/2), sqrt 2) */
-    float m = u32_as_f32((ix & 0x007fffffu) + 0x3f3504f3u);
-    float r = m - 1.0f;
-    /* ln(1+r) = r - r^2/2 + r^3 Q(r) */
-    float Q = -0x1.38b2a8p-4f;
-    Q = fmaf(Q, r, 0x1.055ad8p-3f);
-    Q = fmaf(Q, r, -0x1.0d8586p-3f);
-    Q = fmaf(Q, r, 0x1.22da36p-3f);
-    Q = fmaf(Q, r, -0x1.547240p-3f);
-    Q = fmaf(Q, r, 0x1.99a008p-3f);
-    Q = fmaf(Q, r, -0x1.000228p-2f);
-    Q = fmaf(Q, r, 0x1.555554p-2f);
-    float r2 = r * r;
-    float r3 = r2 * r;
-    float lnm = fmaf(r3, Q, fmaf(-0.5f, r2, r));
-    float lnu = fmaf((float)e, 0x1.62e430p-1f, lnm);    /* + e * ln 2 */
-    float t = -2.0f * lnu;
-    float rho = sqrtf(t);                                /* correctly rounded */
+    const uint32_t k = 2u * (ra >> 9) + 1u;
+    const float uf = (float)(k << 8);                     /* exact: 24 significant bits */
+    const uint32_t b = f32_as_u32(uf);
+    const uint32_t E = b >> 23;                           /* 135 .. 158 */
+    const float nf = (float)((int32_t)(E >> 1) - 79);     /* u = m * 4^n */
+    const float m = u32_as_f32((b & 0x00FFFFFFu) | 0x3F000000u);
+    const uint32_t i = (b >> 15) & 0x1FFu;
+    float inv, l;
+    ln_pivot(i, &inv, &l);
+    const float r = fmaf(m, inv, -1.0f);
+    const float base = fmaf(nf, -0x1.62e430p+1f, l);      /* n * (-4 ln 2) + l_i */
+    float P = fmaf(r, -0x1.555556p-1f, 1.0f);             /* 1 - (2/3) r */
+    P = fmaf(P, r, -2.0f);
+    const float t = fmaf(r, P, base);
+    const float rho = sqrtf(t);                           /* correctly rounded */
 
-    /* angle: fold the quarter turn at its middle so the polynomials only see [0, 1/2] */
-    uint32_t k = (rb >> 6) & 0xFFFFFFu;
-    int fold = k >= 0x800000u;
-    uint32_t kf = fold ? 0x1000000u - k : k;
-    float f = (float)kf * 0x1p-24f;                      /* exact */
-    float w = f * f;
-    float S = -0x1.2d9302p-8f;                           /* sin(pi f/2) = f * S(w) */
-    S = fmaf(S, w, 0x1.465e92p-4f);
-    S = fmaf(S, w, -0x1.4abbbap-1f);
+    /* angle: x in [-1, 1], w = x^2 */
+    const float x = (float)(int32_t)rb * 0x1p-31f;        /* the conversion rounds to nearest even; the scaling is exact */
+    const float w = x * x;
+    float S = 0x1.3e17cap-13f;                            /* sin(pi x/2) = x * S(w) */
+    S = fmaf(S, w, -0x1.32535ap-8f);
+    S = fmaf(S, w, 0x1.4668f2p-4f);
+    S = fmaf(S, w, -0x1.4abbc4p-1f);
     S = fmaf(S, w, 0x1.921fb6p+0f);
-    float sn = f * S;
-    float Cc = 0x1.d9f7b8p-11f;                          /* cos(pi f/2) = 1 + w * C(w) */
-    Cc = fmaf(Cc, w, -0x1.55c664p-6f);
-    Cc = fmaf(Cc, w, 0x1.03c1dep-2f);
+    const float sn = x * S;
+    float Cc = -0x1.93c734p-16f;                          /* cos(pi x/2) = 1 + w * C(w) */
+    Cc = fmaf(Cc, w, 0x1.e173cap-11f);
+    Cc = fmaf(Cc, w, -0x1.55d268p-6f);
+    Cc = fmaf(Cc, w, 0x1.03c1eep-2f);
     Cc = fmaf(Cc, w, -0x1.3bd3ccp+0f);
-    float cs = fmaf(w, Cc, 1.0f);
-    if (fold) { float tmp = cs; cs = sn; sn = tmp; }     /* cos(x) = sin(pi/2 - x) */
-    /* rotate by q quarter turns */
-    uint32_t q = rb >> 30;
-    float c, s;
-    switch (q) {
-    case 0: c = cs;  s = sn;  break;
-    case 1: c = -sn; s = cs;  break;
-    case 2: c = -cs; s = -sn; break;
-    default: c = sn; s = -cs; break;
-    }
-    *z0 = rho * c;
-    *z1 = rho * s;
+    const float cs = fmaf(w, Cc, 1.0f);
+    /* z0 takes its sign from bit 8 of ra (the magnitude's own sign bit, which can be set by a rounding
+     * error of cs at |x| = 1, is dropped) */
+    const uint32_t mag = f32_as_u32(rho * cs) & 0x7FFFFFFFu;
+    *z0 = u32_as_f32(mag | ((ra << 23) & 0x80000000u));
+    *z1 = rho * sn;
 }
 
 /* The transform alone over an array of word pairs: z[2i], z[2i+1] from words[2i], words[2i+1]. */

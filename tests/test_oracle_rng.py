@@ -47,10 +47,23 @@ def test_philox_fewer_rounds_differ():
 
 
 def _closed_form(ra, rb):
+    """The transform's definition, in fp64: u = (2 (ra >> 9) + 1) 2^-24, radius sqrt(-2 ln u); the angle is a quarter turn
+    times x, x = the fp32 nearest to rb read as a signed integer, times 2^-31; z1 = radius sin, z0 = -+radius cos with
+    the sign in bit 8 of ra."""
     u = (2 * (ra >> 9) + 1) / 2.0**24
-    ang = ((rb >> 30) + ((rb >> 6) & 0xFFFFFF) / 2.0**24) * (np.pi / 2)
+    signed = rb - (1 << 32) if rb >= (1 << 31) else rb
+    ang = float(np.float32(signed)) * 2.0**-31 * (np.pi / 2)
     rho = np.sqrt(-2.0 * np.log(u))
-    return rho * np.cos(ang), rho * np.sin(ang)
+    return (-1.0 if (ra >> 8) & 1 else 1.0) * rho * np.cos(ang), rho * np.sin(ang)
+
+
+def _closed_form_arrays(ra, rb):
+    """The same over uint32 arrays."""
+    u = (2.0 * (ra >> np.uint32(9)).astype(np.float64) + 1.0) * 2.0**-24
+    ang = rb.view(np.int32).astype(np.float32).astype(np.float64) * 2.0**-31 * (np.pi / 2)
+    rho = np.sqrt(-2.0 * np.log(u))
+    sign = np.where((ra >> np.uint32(8)) & np.uint32(1), -1.0, 1.0)
+    return sign * rho * np.cos(ang), rho * np.sin(ang), rho
 
 
 def test_counter_layout_words_to_elements():
@@ -68,8 +81,10 @@ def test_counter_layout_words_to_elements():
 
 def test_normal_pair_matches_closed_form_everywhere():
     rng = np.random.default_rng(11)
-    ras = list(rng.integers(0, 2**32, 20000)) + [0, 1 << 9, 0xFFFFFFFF, 0xFFFFFE00, 0x80000000, 0x7FFFFFFF]
-    rbs = list(rng.integers(0, 2**32, 20000)) + [0, 0x3FFFFFC0, 0x20000000, 0x1FFFFFC0, 0x40000000, 0xFFFFFFFF]
+    ras = list(rng.integers(0, 2**32, 20000)) + [0, 1 << 9, 0xFFFFFFFF, 0xFFFFFE00, 0x80000000, 0x7FFFFFFF, 0x100, 0xFFFFFEFF,
+                                                 0xFF800000, 0xFF7FFE00]
+    rbs = list(rng.integers(0, 2**32, 20000)) + [0, 0x7FFFFFFF, 0x80000000, 0xFFFFFFFF, 0x40000000, 0xC0000000, 1, 0x7FFFFF80,
+                                                 0x7FFFFFC0, 0x80000040]
     worst = 0.0
     for ra, rb in zip(ras, rbs):
         ra, rb = int(ra), int(rb)
@@ -81,6 +96,40 @@ def test_normal_pair_matches_closed_form_everywhere():
     assert worst < 4 * 2.0**-23, worst
 
 
+def test_every_radius_code_matches_closed_form():
+    """All 2^23 values of u (ra >> 9), both signs of the cosine: z0 = -+sqrt(-2 ln u) at angle 0, within 2 ulp."""
+    ra = np.arange(2**23, dtype=np.uint64).astype(np.uint32) << np.uint32(9)
+    ra |= (np.arange(2**23, dtype=np.uint32) & np.uint32(1)) << np.uint32(8)        # alternate the sign bit
+    words = np.empty(2 * ra.size, dtype=np.uint32)
+    words[0::2] = ra
+    words[1::2] = 0
+    z = zo.normal_pairs(words)
+    c0, _, rho = _closed_form_arrays(ra, np.zeros_like(ra))
+    assert np.all(z[1::2] == 0)
+    assert np.all(np.signbit(z[0::2]) == (c0 < 0))
+    err = np.abs(z[0::2].astype(np.float64) - c0) / np.spacing(rho.astype(np.float32)).astype(np.float64)
+    assert err.max() < 2.0, (err.max(), int(err.argmax()))
+    # the radius shrinks as u grows: a wrong pivot or a swapped table entry would break the order somewhere
+    mag = np.abs(z[0::2])
+    assert np.all(mag[1:] <= mag[:-1]) and mag[0] == np.float32(np.sqrt(48 * np.log(2))) and mag[-1] > 0
+
+
+def test_every_angle_code_matches_closed_form():
+    """All 2^24 angles rb = i << 8 (every value of the top 24 bits, both signs) at a fixed radius: absolute error of
+    (cos, sin) within 3 fp32 ulps of 1, and cos^2 + sin^2 = 1."""
+    rb = np.arange(2**24, dtype=np.uint64).astype(np.uint32) << np.uint32(8)
+    ra = np.full(rb.size, 0x9B17A400, dtype=np.uint32)             # u = 0.6058..., radius about 1
+    words = np.empty(2 * rb.size, dtype=np.uint32)
+    words[0::2] = ra
+    words[1::2] = rb
+    z = zo.normal_pairs(words).astype(np.float64)
+    c0, c1, rho = _closed_form_arrays(ra, rb)
+    assert 0.99 < rho[0] < 1.01
+    assert np.max(np.abs(z[0::2] - c0)) < 3 * 2.0**-23 and np.max(np.abs(z[1::2] - c1)) < 3 * 2.0**-23
+    assert np.max(np.abs((z[0::2]**2 + z[1::2]**2) / rho**2 - 1)) < 1e-6
+    assert np.all(z[1::2][1:2**23] > 0) and np.all(z[1::2][2**23:] < 0) and z[1] == 0        # the sine carries the sign of rb
+
+
 def test_normal_radius_identity_and_extremes():
     # z0^2 + z1^2 = -2 ln u, largest radius at u = 2^-24, smallest at u = 1 - 2^-24
     for ra, rb in [(0, 0x12345678), (0xFFFFFFFF, 0x9ABCDEF0), (0x40000000, 0)]:
@@ -89,9 +138,20 @@ def test_normal_radius_identity_and_extremes():
         assert abs((float(z0)**2 + float(z1)**2) / (-2 * np.log(u)) - 1) < 1e-6
     z0, z1 = zo.normal_pair(0, 0)
     assert abs(float(z0) - np.sqrt(2 * 24 * np.log(2))) < 1e-5 and z1 == 0
-    # quadrants: rb = q<<30 with zero fraction gives the four axis directions
-    dirs = [np.sign(zo.normal_pair(0, q << 30)).tolist() for q in range(4)]
-    assert [[float(a) + 0.0, float(b) + 0.0] for a, b in dirs] == [[1, 0], [0, 1], [-1, 0], [0, -1]]
+    z0, z1 = zo.normal_pair(0xFFFFFE00, 0)
+    assert abs(float(z0) / np.sqrt(-2 * np.log1p(-2.0**-24)) - 1) < 1e-6
+    # directions: angle 0 is the +-z0 axis (sign in bit 8 of ra), a quarter turn either way the +-z1 axis, and the
+    # four sign combinations at an eighth of a turn land in the four quadrants
+    s = float(np.sqrt(2 * 24 * np.log(2)))
+    assert [float(v) for v in zo.normal_pair(0x100, 0)] == [-float(np.float32(s)), 0.0]
+    z0, z1 = zo.normal_pair(0, 0x7FFFFFFF)
+    assert abs(float(z1) - s) < 1e-5 and abs(float(z0)) < 1e-6
+    z0, z1 = zo.normal_pair(0, 0x80000000)
+    assert abs(float(z1) + s) < 1e-5 and abs(float(z0)) < 1e-6
+    quads = [np.sign(zo.normal_pair(ra, rb)).tolist() for ra in (0, 0x100) for rb in (0x40000000, 0xC0000000)]
+    assert quads == [[1, 1], [1, -1], [-1, 1], [-1, -1]]
+    z0, z1 = zo.normal_pair(0, 0x40000000)
+    assert abs(float(z0) - s / np.sqrt(2)) < 1e-5 and abs(float(z1) - s / np.sqrt(2)) < 1e-5
 
 
 def test_z_is_standard_normal():

@@ -115,12 +115,14 @@ def test_g_against_autograd_on_the_tiny_config():
     # (the ReLU kinks of 32768 hidden units are dense around theta: the limit is only clean well below 1e-6)
     assert abs(g_exact(1e-8) / want - 1) < 1e-6
     # (ii) the oracle's step, which rounds theta +- eps z into fp32 storage, computes that same Eq. 1
-    #      at the configured eps (where the cubic term of this loss is already ~10 %: a property of the
-    #      workload, eps |z| = 0.37 against weights of size 0.02, not of the code)
+    #      at the configured eps.  There the loss is far from linear along z (eps |z| reaches 0.37 against weights
+    #      of size 0.02 and 32768 ReLU kinks lie in between: g(eps) for this z runs 0.26, 0.49, 0.69, 0.65, 0.56 at
+    #      eps = 1e-3, 5e-4, 2.5e-4, 1e-4, 1e-5 towards the derivative 0.53), a property of the workload, not of
+    #      the code: only sign and order of magnitude are asked of it
     lp, lm = zo.dual_loss_fused(cfg, theta, tokens, 42, c["eps"])
     g = zo.projected_gradient(lp, lm, c["eps"])
     assert abs(g / g_exact(float(np.float32(c["eps"]))) - 1) < 1e-5, (g, want)
-    assert abs(g / want - 1) < 0.2
+    assert 1 / 3 < g / want < 3
 
 
 def test_g_is_even_in_eps_and_converges_quadratically():
@@ -146,7 +148,7 @@ def test_g_is_even_in_eps_and_converges_quadratically():
 @pytest.mark.parametrize("literal", [False, True])
 def test_alg2_deferred_update_equals_immediate(dtype, literal):
     cfg, theta, tokens = _micro(dtype)
-    eps, lr = 1e-3, (1e-2 if dtype == zo.FP32 else 3e-1)
+    eps, lr = 1e-3, (1e-2 if dtype == zo.FP32 else 1e-1)
     imm = [t.copy() for t in theta]
     dfr = [t.copy() for t in theta]
     runner = zo.Alg2Runner(cfg, dfr, eps, lr, literal=literal)
