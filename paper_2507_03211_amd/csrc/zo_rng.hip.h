@@ -5,11 +5,14 @@
 // (s, t, i), so "reset the generator to seed s" costs nothing and any kernel can regenerate
 // exactly the values another one used.  Generator: Philox4x32-10 (Salmon et al., SC'11), one
 // block per four consecutive elements.  Transform: pair-wise Box-Muller whose fp32 arithmetic
-// is fixed operation by operation (only IEEE add, mul, fma, sqrt and integer ops), so the bits
-// are the same on any IEEE-754 machine.  Must be compiled with -ffp-contract=off.
+// is fixed operation by operation (only IEEE conversions, mul, fma, sqrt, integer ops and one
+// lookup in a 512-entry table of fp32 constants), so the bits are the same on any IEEE-754
+// machine.  Must be compiled with -ffp-contract=off.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "zo_ln_table.hip.h"
 
 namespace zo {
 
@@ -20,6 +23,21 @@ __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t k)
 {
     uint32_t r;
     asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0x96" : "=v"(r) : "v"(a), "v"(b), "s"(k));
+    return r;
+}
+
+// (a & m) | o in one instruction; m and o are wave-uniform constants.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t m, uint32_t o)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(m), "v"(o));
+    return r;
+}
+// Bits of `a` where the wave-uniform mask m is set, bits of `b` elsewhere, in one instruction.
+__device__ __forceinline__ uint32_t bit_select(uint32_t m, uint32_t a, uint32_t b)
+{
+    uint32_t r;
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "s"(m), "v"(a), "v"(b));
     return r;
 }
 
@@ -69,66 +87,61 @@ __device__ __forceinline__ float sqrt_rn(float t)
     return __builtin_fmaf(d, h, g);
 }
 
-// Two standard normals from two words.  u = (2 (ra>>9) + 1) 2^-24 in (0,1); the angle is
-// (rb>>30) quarter turns plus the 24-bit fraction (rb>>6) of one.
-__device__ __forceinline__ void normal_pair(uint32_t ra, uint32_t rb, float &z0, float &z1)
+// The logarithm's pivot table in LDS: 512 {inv_i, l_i} pairs, 4 KiB.  Every kernel that draws normals copies it
+// from constant memory once per workgroup (256 threads x 16 bytes) and synchronises before the first draw.
+constexpr int kLnPivots = 512;
+__device__ __forceinline__ void load_ln_pivots(float2 *tab /* LDS, kLnPivots entries */)
 {
-    // radius^2 = -2 ln u, with u = m 2^e and m in [sqrt(1/2), sqrt(2))
-    // (the factor 2^-24 is taken off the exponent field instead of multiplied in: 24 << 23 = 0x0c000000)
-    const float u24 = (float)(2u * (ra >> 9) + 1u);
-    const uint32_t ix = __float_as_uint(u24) - (0x3f3504f3u + 0x0c000000u);
-    const float ef = (float)((int32_t)ix >> 23);
-    const float m = __uint_as_float((ix & 0x007fffffu) + 0x3f3504f3u);
-    const float r = m - 1.0f;
-    // The radius needs t = -2 ln u.  The factor -2 is carried through the sum instead of multiplied in at the end:
-    // every coefficient below is -2 times that of ln(1+r) = r - r^2/2 + r^3 q(r), and a power of two scales
-    // every intermediate exactly, so t has the bits of -2 * (e ln 2 + ln m) evaluated step by step.
-    float q = 0x1.38b2a8p-3f;
-    q = __builtin_fmaf(q, r, -0x1.055ad8p-2f);
-    q = __builtin_fmaf(q, r, 0x1.0d8586p-2f);
-    q = __builtin_fmaf(q, r, -0x1.22da36p-2f);
-    q = __builtin_fmaf(q, r, 0x1.547240p-2f);
-    q = __builtin_fmaf(q, r, -0x1.99a008p-2f);
-    q = __builtin_fmaf(q, r, 0x1.000228p-1f);
-    q = __builtin_fmaf(q, r, -0x1.555554p-1f);
-    const float r2 = r * r;
-    const float r3 = r2 * r;
-    const float lnm = __builtin_fmaf(r3, q, __builtin_fmaf(-2.0f, r, r2));
-    const float rho = sqrt_rn(__builtin_fmaf(ef, -0x1.62e430p+0f, lnm));
-
-    // quarter-turn fraction folded at its middle: polynomials see [0, 1/2]
-    const uint32_t k = (rb >> 6) & 0xFFFFFFu;
-    const bool fold = k >= 0x800000u;
-    const float f = (float)(fold ? 0x1000000u - k : k) * 0x1p-24f;
-    const float w = f * f;
-    float sp = -0x1.2d9302p-8f;                      // sin(pi f / 2) = f sp(w)
-    sp = __builtin_fmaf(sp, w, 0x1.465e92p-4f);
-    sp = __builtin_fmaf(sp, w, -0x1.4abbbap-1f);
-    sp = __builtin_fmaf(sp, w, 0x1.921fb6p+0f);
-    const float sn = f * sp;
-    float cp = 0x1.d9f7b8p-11f;                      // cos(pi f / 2) = 1 + w cp(w)
-    cp = __builtin_fmaf(cp, w, -0x1.55c664p-6f);
-    cp = __builtin_fmaf(cp, w, 0x1.03c1dep-2f);
-    cp = __builtin_fmaf(cp, w, -0x1.3bd3ccp+0f);
-    const float cs = __builtin_fmaf(w, cp, 1.0f);
-    // after the fold cos and sin trade places; an odd number of quarter turns trades them again
-    const uint32_t quad = rb >> 30;
-    const bool swap = fold != ((quad & 1u) != 0u);
-    float c = swap ? sn : cs;
-    float s = swap ? cs : sn;
-    // signs per quadrant: (+,+), (-,+), (-,-), (+,-)
-    const uint32_t csign = ((quad + 1u) & 2u) << 30;
-    const uint32_t ssign = (quad & 2u) << 30;
-    c = __uint_as_float(__float_as_uint(c) ^ csign);
-    s = __uint_as_float(__float_as_uint(s) ^ ssign);
-    z0 = rho * c;
-    z1 = rho * s;
+    for (int i = threadIdx.x; i < kLnPivots / 2; i += blockDim.x)
+        ((float4 *)tab)[i] = ((const float4 *)kLnPivot)[i];
+    __syncthreads();
 }
 
-__device__ __forceinline__ void normal4(const u32x4 &wd, float z[4])
+// Two standard normals from two words.
+//   radius  u = (2 (ra >> 9) + 1) 2^-24 in (0,1), rho = sqrt(-2 ln u)
+//   angle   x = (float)(int32)rb 2^-31 in [-1, 1], a quarter turn either way
+//   z1 = rho sin(pi x / 2);  z0 = -+rho cos(pi x / 2), negative when bit 8 of ra is set.
+// The logarithm: uf = (float)(k 2^8) (exact) has the biased exponent E; u = m 4^n with n = (E >> 1) - 79 and m, the
+// significand of uf under the exponent 126 + (E & 1), in [0.5, 2).  Bits 23..15 of uf select one of 512 significand
+// intervals with pivot p_i (its midpoint; 1 for the interval that ends at m = 1); r = m inv_i - 1 is at most 2^-9 and
+//   -2 ln u = n (-4 ln 2) + l_i + r (-2 + r (1 - (2/3) r))
+// with {inv_i, l_i} = {fl(1 / p_i), fl(2 ln inv_i)} from the table.  A table lookup and three fused multiply-adds
+// take the place of a ten-term logarithm polynomial; sign bits take the place of quadrant logic.
+__device__ __forceinline__ void normal_pair(uint32_t ra, uint32_t rb, float &z0, float &z1, const float2 *tab)
 {
-    normal_pair(wd.x, wd.y, z[0], z[1]);
-    normal_pair(wd.z, wd.w, z[2], z[3]);
+    const float uf = (float)and_or(ra, 0xFFFFFE00u, 0x100u);
+    const uint32_t b = __float_as_uint(uf);
+    const float nf = (float)(b >> 24) - 79.0f;
+    const float m = __uint_as_float((b & 0x00FFFFFFu) | 0x3F000000u);
+    const float2 pv = tab[(b >> 15) & 0x1FFu];
+    const float r = __builtin_fmaf(m, pv.x, -1.0f);
+    const float base = __builtin_fmaf(nf, -0x1.62e430p+1f, pv.y);
+    float p = __builtin_fmaf(r, -0x1.555556p-1f, 1.0f);
+    p = __builtin_fmaf(p, r, -2.0f);
+    const float rho = sqrt_rn(__builtin_fmaf(r, p, base));
+
+    const float x = (float)(int32_t)rb * 0x1p-31f;
+    const float w = x * x;
+    float sp = 0x1.3e17cap-13f;                      // sin(pi x / 2) = x sp(w)
+    sp = __builtin_fmaf(sp, w, -0x1.32535ap-8f);
+    sp = __builtin_fmaf(sp, w, 0x1.4668f2p-4f);
+    sp = __builtin_fmaf(sp, w, -0x1.4abbc4p-1f);
+    sp = __builtin_fmaf(sp, w, 0x1.921fb6p+0f);
+    float cp = -0x1.93c734p-16f;                     // cos(pi x / 2) = 1 + w cp(w)
+    cp = __builtin_fmaf(cp, w, 0x1.e173cap-11f);
+    cp = __builtin_fmaf(cp, w, -0x1.55d268p-6f);
+    cp = __builtin_fmaf(cp, w, 0x1.03c1eep-2f);
+    cp = __builtin_fmaf(cp, w, -0x1.3bd3ccp+0f);
+    const float cs = __builtin_fmaf(w, cp, 1.0f);
+    z1 = rho * (x * sp);
+    // magnitude of rho cos with the sign taken from bit 8 of ra (one bit-field insert)
+    z0 = __uint_as_float(bit_select(0x7FFFFFFFu, __float_as_uint(rho * cs), ra << 23));
+}
+
+__device__ __forceinline__ void normal4(const u32x4 &wd, float z[4], const float2 *tab)
+{
+    normal_pair(wd.x, wd.y, z[0], z[1], tab);
+    normal_pair(wd.z, wd.w, z[2], z[3], tab);
 }
 
 }  // namespace zo

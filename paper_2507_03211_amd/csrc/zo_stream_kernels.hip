@@ -15,11 +15,13 @@ namespace zo {
 // ------------------------------------------------------------------ z only (verification)
 __global__ __launch_bounds__(256) void z_kernel(float *out, uint64_t n, uint64_t seed, uint32_t tid, uint64_t first)
 {
+    __shared__ float2 ln_tab[kLnPivots];
+    load_ln_pivots(ln_tab);
     // one Philox block per thread; blocks first/4 .. (first+n-1)/4
     const uint64_t j = first / 4 + (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (4 * j >= first + n) return;
     float z[4];
-    normal4(philox_block(seed, tid, j), z);
+    normal4(philox_block(seed, tid, j), z, ln_tab);
 #pragma unroll
     for (int l = 0; l < 4; ++l) {
         const uint64_t i = 4 * j + l;
@@ -29,10 +31,12 @@ __global__ __launch_bounds__(256) void z_kernel(float *out, uint64_t n, uint64_t
 
 __global__ __launch_bounds__(256) void normal_pairs_kernel(const uint32_t *words, float *z, uint64_t n_pairs)
 {
+    __shared__ float2 ln_tab[kLnPivots];
+    load_ln_pivots(ln_tab);
     const uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= n_pairs) return;
     float a, b;
-    normal_pair(words[2 * p], words[2 * p + 1], a, b);
+    normal_pair(words[2 * p], words[2 * p + 1], a, b, ln_tab);
     z[2 * p] = a;
     z[2 * p + 1] = b;
 }
@@ -76,8 +80,17 @@ template <int DT> __device__ __forceinline__ uint4 pack16(const float *f)
     } else {
         uint32_t w[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            w[i] = (uint32_t)Prec<DT>::f2w(f[2 * i]) | ((uint32_t)Prec<DT>::f2w(f[2 * i + 1]) << 16);
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (DT == kBF16) {
+                // both halves of a word in one conversion instruction (round to nearest even, as f2w does one by one)
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                const bf16x2 pk = __builtin_convertvector(f32x2{f[2 * i], f[2 * i + 1]}, bf16x2);
+                w[i] = __builtin_bit_cast(uint32_t, pk);
+            } else {
+                w[i] = (uint32_t)Prec<DT>::f2w(f[2 * i]) | ((uint32_t)Prec<DT>::f2w(f[2 * i + 1]) << 16);
+            }
+        }
         return uint4{w[0], w[1], w[2], w[3]};
     }
 }
@@ -92,6 +105,8 @@ __global__ __launch_bounds__(256) void axpy_z_kernel(const TensorDesc *__restric
 {
     using W = typename Prec<DT>::W;
     constexpr int VN = Vec16<DT>::N;
+    __shared__ float2 ln_tab[kLnPivots];
+    load_ln_pivots(ln_tab);
     TensorDesc d;
     const uint64_t chunk = (uint64_t)blockIdx.x + chunk_offset;
     if (descs) {
@@ -118,7 +133,7 @@ __global__ __launch_bounds__(256) void axpy_z_kernel(const TensorDesc *__restric
             const uint64_t i0 = base + (uint64_t)(it * 256 + threadIdx.x) * VN;
             float z[VN];
 #pragma unroll
-            for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b);
+            for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
             float th[VN];
             unpack16<DT>(*(const uint4 *)(src + i0), th);
 #pragma unroll
@@ -143,7 +158,7 @@ __global__ __launch_bounds__(256) void axpy_z_kernel(const TensorDesc *__restric
         if (i0 >= d.numel) break;
         float z[VN];
 #pragma unroll
-        for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b);
+        for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
         uint32_t rw[SR ? VN : 1];
         if constexpr (SR) {
 #pragma unroll
@@ -179,6 +194,8 @@ __global__ __launch_bounds__(256) void axpy_z_multi_kernel(const TensorDesc *__r
 {
     using W = typename Prec<DT>::W;
     constexpr int VN = Vec16<DT>::N;
+    __shared__ float2 ln_tab[kLnPivots];
+    load_ln_pivots(ln_tab);
     const uint64_t chunk = (uint64_t)blockIdx.x + chunk_offset;
     int lo = 0, hi = n_desc - 1;                      // last descriptor whose first_chunk <= chunk
     while (lo < hi) {
@@ -207,7 +224,7 @@ __global__ __launch_bounds__(256) void axpy_z_multi_kernel(const TensorDesc *__r
             const float sc = dev_scale[j];
             float z[VN];
 #pragma unroll
-            for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b);
+            for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
 #pragma unroll
             for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
             if constexpr (SR) {
@@ -246,6 +263,8 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
     using W = typename Prec<DT>::W;
     constexpr int VN = Vec16<DT>::N;
     static_assert(!(SINGLE && UPD != 0) && !(DT == kFP32 && UPD == 2), "no such variant");
+    __shared__ float2 ln_tab[SINGLE ? 1 : kLnPivots];
+    if constexpr (!SINGLE) load_ln_pivots(ln_tab);
     float us = 0.0f;
     if constexpr (UPD != 0) us = *dev_scale;
     int di = 0;
@@ -268,7 +287,7 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
             float z[VN];
             if constexpr (!SINGLE) {
 #pragma unroll
-                for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b);
+                for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
             }
             const bool whole = i0 + VN <= numel;
             if constexpr (SINGLE) {
@@ -284,7 +303,7 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
                 if constexpr (UPD != 0) {
                     float zu[VN];
 #pragma unroll
-                    for (int bk = 0; bk < VN / 4; ++bk) normal4(philox_block(upd_seed, d.tid, i0 / 4 + bk), zu + 4 * bk);
+                    for (int bk = 0; bk < VN / 4; ++bk) normal4(philox_block(upd_seed, d.tid, i0 / 4 + bk), zu + 4 * bk, ln_tab);
 #pragma unroll
                     for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(us, zu[e], th[e]);
                     uint4 stored;
@@ -333,6 +352,7 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
     const uint32_t rb = threadIdx.x / 16, cb = threadIdx.x % 16;
     const uint32_t c = c0 + 4 * cb;
     W vp[4][4], vm[4][4];                           // [row in patch][column in patch]
+    [[maybe_unused]] float fp[4][4], fm[4][4];      // bf16: kept in fp32 until two rows of a column are converted together
     // Rows or columns past the edge of the matrix are computed like the others, from element 0 (always there),
     // and never leave LDS: one straight-line body for the four rows lets the compiler share the generator's
     // constants between them instead of setting them up again behind every bounds branch.
@@ -349,10 +369,10 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
             for (int e = 0; e < 4; ++e) vp[it][e] = raw[e];
         } else {
             float z[4];
-            normal4(philox_block(seed, d.tid, i0 / 4), z);
+            normal4(philox_block(seed, d.tid, i0 / 4), z, ln_tab);
             if constexpr (UPD != 0) {
                 float zu[4];
-                normal4(philox_block(upd_seed, d.tid, i0 / 4), zu);
+                normal4(philox_block(upd_seed, d.tid, i0 / 4), zu, ln_tab);
                 u32x4 rr{};
                 if constexpr (UPD == 2) rr = philox_block(upd_seed, d.tid, i0 / 4, 3u);
                 const uint32_t rw[4] = {rr.x, rr.y, rr.z, rr.w};
@@ -370,16 +390,30 @@ __global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t s
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float th = Prec<DT>::w2f(raw[e]);
-                vp[it][e] = Prec<DT>::f2w(__builtin_fmaf(eps, z[e], th));
-                vm[it][e] = Prec<DT>::f2w(__builtin_fmaf(-eps, z[e], th));
+                if constexpr (DT == kBF16) {
+                    fp[it][e] = __builtin_fmaf(eps, z[e], th);
+                    fm[it][e] = __builtin_fmaf(-eps, z[e], th);
+                } else {
+                    vp[it][e] = Prec<DT>::f2w(__builtin_fmaf(eps, z[e], th));
+                    vm[it][e] = Prec<DT>::f2w(__builtin_fmaf(-eps, z[e], th));
+                }
             }
         }
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
+        W *dstp = sp + (4 * cb + e) * LD + 4 * rb, *dstm = sm + (4 * cb + e) * LD + 4 * rb;
+        if constexpr (DT == kBF16 && !SINGLE) {
+            // one conversion instruction rounds two rows of the column (nearest even, as the scalar conversion does)
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            auto pk = [](float lo, float hi) { return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2)); };
+            *(uint2 *)dstp = uint2{pk(fp[0][e], fp[1][e]), pk(fp[2][e], fp[3][e])};
+            *(uint2 *)dstm = uint2{pk(fm[0][e], fm[1][e]), pk(fm[2][e], fm[3][e])};
+            continue;
+        }
         W colp[4] = {vp[0][e], vp[1][e], vp[2][e], vp[3][e]};
         W colm[4] = {vm[0][e], vm[1][e], vm[2][e], vm[3][e]};
-        W *dstp = sp + (4 * cb + e) * LD + 4 * rb, *dstm = sm + (4 * cb + e) * LD + 4 * rb;
         if constexpr (sizeof(W) == 2) {
             *(uint2 *)dstp = *(const uint2 *)colp;
             if constexpr (!SINGLE) *(uint2 *)dstm = *(const uint2 *)colm;

@@ -27,23 +27,41 @@ def test_z_bits_exact(seed, tid, first, n):
     assert got.tobytes() == want.tobytes()
 
 
-def test_normal_transform_bits_exact_over_all_radii_and_angle_edges():
-    # every one of the 2^23 radius codes once, with pseudo-random angles; then every quadrant / fold edge
-    rng = np.random.Generator(np.random.PCG64(5))
-    ra = (np.arange(1 << 23, dtype=np.uint64) << 9).astype(np.uint32)
-    rb = rng.integers(0, 2**32, size=ra.size, dtype=np.uint64).astype(np.uint32)
-    edge_k = np.array([0, 1, 2, 0x7FFFFF, 0x800000, 0x800001, 0xFFFFFE, 0xFFFFFF], dtype=np.uint32)
-    eb = np.array([(q << 30) | (k << 6) | low for q in range(4) for k in edge_k for low in (0, 63)], dtype=np.uint32)
-    ea = rng.integers(0, 2**32, size=eb.size, dtype=np.uint64).astype(np.uint32)
-    words = np.empty(2 * (ra.size + eb.size), dtype=np.uint32)
-    words[0::2] = np.concatenate([ra, ea])
-    words[1::2] = np.concatenate([rb, eb])
+def _pairs_gpu(words):
     dev_words = torch.from_numpy(words.view(np.int32)).to(DEV)
     out = torch.empty(words.size, dtype=torch.float32, device=DEV)
     zo_amd.zo_kernel_normal_pairs(dev_words, out, words.size // 2)
     torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def test_normal_transform_bits_exact_over_all_radii_and_angle_edges():
+    # every one of the 2^23 radius codes once (the cosine's sign bit alternating), with pseudo-random angles; then the
+    # angle's edge cases: zero, the quarter turns, both signs, integers that the conversion to fp32 rounds (ties too)
+    rng = np.random.Generator(np.random.PCG64(5))
+    ra = (np.arange(1 << 23, dtype=np.uint64) << 9).astype(np.uint32) | ((np.arange(1 << 23, dtype=np.uint32) & np.uint32(1)) << np.uint32(8))
+    rb = rng.integers(0, 2**32, size=ra.size, dtype=np.uint64).astype(np.uint32)
+    edge = [0, 1, 2, 0x7F, 0x80, 0x81, 0x01000000, 0x01000001, 0x01000002, 0x01000003, 0x3FFFFFFF, 0x40000000, 0x40000020, 0x40000040,
+            0x40000060, 0x7FFFFF80, 0x7FFFFFBF, 0x7FFFFFC0, 0x7FFFFFFF]
+    eb = np.array(edge + [(-v) & 0xFFFFFFFF for v in edge] + [0x80000000, 0x80000001, 0xC0000000], dtype=np.uint32)
+    ea = rng.integers(0, 2**32, size=eb.size, dtype=np.uint64).astype(np.uint32)
+    words = np.empty(2 * (ra.size + eb.size), dtype=np.uint32)
+    words[0::2] = np.concatenate([ra, ea])
+    words[1::2] = np.concatenate([rb, eb])
     want = zo.normal_pairs(words)
-    got = out.cpu().numpy()
+    got = _pairs_gpu(words)
+    assert got.tobytes() == want.tobytes(), np.flatnonzero(got.view(np.uint32) != want.view(np.uint32))[:10]
+
+
+def test_normal_transform_bits_exact_over_all_angle_codes():
+    # all 2^26 values of the angle word's top 26 bits (rb = i << 6: every fp32 the conversion can give from them, both
+    # signs) in one launch, the radius code walking through its range beside them
+    i = np.arange(1 << 26, dtype=np.uint64)
+    words = np.empty(2 << 26, dtype=np.uint32)
+    words[0::2] = ((i * 2654435761) & 0xFFFFFFFF).astype(np.uint32)
+    words[1::2] = (i << 6).astype(np.uint32)
+    want = zo.normal_pairs(words)
+    got = _pairs_gpu(words)
     assert got.tobytes() == want.tobytes(), np.flatnonzero(got.view(np.uint32) != want.view(np.uint32))[:10]
 
 
