@@ -21,10 +21,10 @@
  * arithmetic is fixed operation by operation, so that "reset the seed" becomes
  * "use the same counters" and the bits can be reproduced on any IEEE-754
  * machine.  The transform is laid out so that a GPU needs few instructions
- * for it (a 512-entry pivot table takes the place of a long logarithm
- * polynomial, the angle's sign bits take the place of quadrant logic); what
- * it computes is the textbook sqrt(-2 ln u) (cos, sin)(angle), which is what
- * the pins check it against.
+ * for it (a table of piecewise cubics takes the place of logarithm and square
+ * root, the angle's sign bits take the place of quadrant logic); what it
+ * computes is the textbook Rayleigh radius times (cos, sin) of a uniform
+ * angle, which is what the pins check it against.
  *
  * Precision: z is DEFINED in fp32 (this is part of the method's specification,
  * not an approximation of something else); the perturbation is one fp32 fused
@@ -32,7 +32,7 @@
  *
  * Pins (tests/test_oracle_rng.py): published Philox known-answer vectors, a
  * second implementation with Python integers, the closed form
- * sqrt(-2 ln u) (cos, sin)(angle) in fp64, moments and a KS test, numpy's
+ * (Rayleigh quantile) x (cos, sin)(angle) in fp64, moments and a KS test, numpy's
  * float16 cast for the half rounding, chunking invariance.
  *
  * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math).
@@ -81,52 +81,64 @@ static float u32_as_f32(uint32_t x) { float f; memcpy(&f, &x, 4); return f; }
 static uint32_t f32_as_u32(float f) { uint32_t x; memcpy(&x, &f, 4); return x; }
 
 /* Two standard normals from two 32-bit words (pair-wise Box-Muller):
- *   u     = (2*(ra>>9)+1) * 2^-24                 in (0,1), 24 significant bits
- *   rho   = sqrt(-2 ln u)
+ *   rho   = a radius with the Rayleigh distribution, drawn by inverting its distribution function
+ *           F(rho) = 1 - exp(-rho^2 / 2) at F uniform over (0,1)   [the textbook rho = sqrt(-2 ln U)]
  *   x     = (float)(int32_t)rb * 2^-31            in [-1, 1]: a quarter turn either way
  *   z1    = rho * sin(pi x / 2)
- *   z0    = +-rho * cos(pi x / 2), negative when bit 8 of ra is set
+ *   z0    = +-rho * cos(pi x / 2), negative when bit 31 of ra is set
  * ((cos, sin) of an angle uniform over the right half circle with an independent fair sign on the
  * cosine is uniform over the circle.)  Every floating-point step is a single IEEE fp32 operation
- * (conversion, mul, fma, sqrt), written out in the order the specification gives it.
+ * (conversion, add, mul, fma), written out in the order the specification gives it.
  *
- * The logarithm.  uf = (float)(k * 2^8), k = 2*(ra>>9)+1, is exact; with E its biased exponent
- * and lb = E & 1, u = m * 4^n where n = (E >> 1) - 79 is in -12..0 and m, the significand of uf
- * under the exponent 126 + lb, is in [0.5, 2).  The 512 intervals of m selected by
- * i = 256 lb + (top 8 fraction bits) each have a pivot p_i: the interval's midpoint,
- *   p_i = (1 + (j + 1/2) / 256) * (lb ? 1 : 1/2),  j = i mod 256,
- * except p_255 = 1 (the interval that ends at m = 1, where -2 ln u goes to zero and has to keep
- * its relative accuracy).  With inv_i = fl(1 / p_i), taken from then on as the exact number it is,
- * and l_i = fl(2 ln inv_i):
- *   r = fma(m, inv_i, -1)                         |r| <= 2^-9, m = (1 + r) / inv_i exactly up to r's rounding
- *   t = -2 ln u = n * (-4 ln 2) + l_i - 2 ln(1 + r)
- * with -2 ln(1 + r) = r * (-2 + r * (1 + r * (-2/3))) + O(r^4). */
-static void ln_pivot(uint32_t i, float *inv, float *l)
+ * The radius.  q = (2 j + 1) 2^-25 with j = bits 30..8 of ra lies in (0, 1/2); bit 4 of ra says which
+ * half of the distribution it measures:
+ *   h = 0:  F = q,       rho = sqrt(-2 ln(1 - q))     (rho below the median)
+ *   h = 1:  1 - F = q,   rho = sqrt(-2 ln q)          (rho above the median)
+ * so that F is uniform over (0,1) and either end is resolved with the relative precision of a
+ * floating-point q.  Both functions are smooth in the RELATIVE position of q inside a binade, so
+ * each is tabulated piecewise: qf = (float)((2 j + 1) 2^7) is exact, its biased exponent E
+ * (134..157) and top five fraction bits jj select one of 24 x 32 cells, the cell's pivot pf is its
+ * midpoint (fraction bits jj, then a one, then zeros), and with d = qf - pf (exact)
+ *   rho = a0 + d (a1 + d (a2 + d a3))
+ * where a_k = fl32 of the k-th Taylor coefficient of rho_h at the pivot with respect to d
+ * (|d| / pf <= 2^-6, the truncation error is below 0.05 ulp).  The coefficients are worked out below
+ * from the derivatives of t = -2 ln g, g = 1 - q or q, and rho = sqrt(t), in double precision. */
+static float rayleigh_cell[2][24 * 32][4];
+
+__attribute__((constructor)) static void rayleigh_cells_init(void)
 {
-    const double j = (double)(i & 255u), half = (i >> 8) ? 1.0 : 0.5;
-    const double p = i == 255u ? 1.0 : (1.0 + (j + 0.5) / 256.0) * half;
-    *inv = (float)(1.0 / p);
-    *l = (float)(2.0 * log((double)*inv));
+    for (int h = 0; h < 2; ++h)
+        for (int E = 134; E < 158; ++E)
+            for (int jj = 0; jj < 32; ++jj) {
+                const double q = ldexp(1.0 + ((double)jj + 0.5) / 32.0, E - 127 - 32);   /* the pivot as a probability */
+                const double g = h ? q : 1.0 - q, dg = h ? 1.0 : -1.0;                  /* g and dg/dq */
+                const double t = h ? -2.0 * log(q) : -2.0 * log1p(-q);
+                const double t1 = -2.0 * dg / g, t2 = 2.0 / (g * g), t3 = -4.0 * dg / (g * g * g);
+                const double rho = sqrt(t);
+                const double r1 = t1 / (2.0 * rho);
+                const double r2 = t2 / (2.0 * rho) - t1 * t1 / (4.0 * rho * rho * rho);
+                const double r3 = t3 / (2.0 * rho) - 3.0 * t1 * t2 / (4.0 * rho * rho * rho)
+                                  + 3.0 * t1 * t1 * t1 / (8.0 * rho * rho * rho * rho * rho);
+                float *a = rayleigh_cell[h][(E - 134) * 32 + jj];
+                /* d counts in units of 2^-32 of q: each derivative order takes one factor 2^-32 */
+                a[0] = (float)rho;
+                a[1] = (float)ldexp(r1, -32);
+                a[2] = (float)ldexp(r2 / 2.0, -64);
+                a[3] = (float)ldexp(r3 / 6.0, -96);
+            }
 }
 
 void zo_oracle_normal_pair(uint32_t ra, uint32_t rb, float *z0, float *z1)
 {
-    /* radius: t = -2 ln u */
-    const uint32_t k = 2u * (ra >> 9) + 1u;
-    const float uf = (float)(k << 8);                     /* exact: 24 significant bits */
-    const uint32_t b = f32_as_u32(uf);
-    const uint32_t E = b >> 23;                           /* 135 .. 158 */
-    const float nf = (float)((int32_t)(E >> 1) - 79);     /* u = m * 4^n */
-    const float m = u32_as_f32((b & 0x00FFFFFFu) | 0x3F000000u);
-    const uint32_t i = (b >> 15) & 0x1FFu;
-    float inv, l;
-    ln_pivot(i, &inv, &l);
-    const float r = fmaf(m, inv, -1.0f);
-    const float base = fmaf(nf, -0x1.62e430p+1f, l);      /* n * (-4 ln 2) + l_i */
-    float P = fmaf(r, -0x1.555556p-1f, 1.0f);             /* 1 - (2/3) r */
-    P = fmaf(P, r, -2.0f);
-    const float t = fmaf(r, P, base);
-    const float rho = sqrtf(t);                           /* correctly rounded */
+    /* radius */
+    const float qf = (float)((ra & 0x7FFFFF00u) | 0x80u);  /* (2 j + 1) 2^7, exact: 24 significant bits */
+    const uint32_t b = f32_as_u32(qf);
+    const float pf = u32_as_f32((b & 0xFFFC0000u) | 0x00020000u);
+    const float d = qf - pf;                               /* exact */
+    const float *a = rayleigh_cell[(ra >> 4) & 1u][(b >> 18) - 134u * 32u];
+    float rho = fmaf(a[3], d, a[2]);
+    rho = fmaf(rho, d, a[1]);
+    rho = fmaf(rho, d, a[0]);
 
     /* angle: x in [-1, 1], w = x^2 */
     const float x = (float)(int32_t)rb * 0x1p-31f;        /* the conversion rounds to nearest even; the scaling is exact */
@@ -143,10 +155,10 @@ void zo_oracle_normal_pair(uint32_t ra, uint32_t rb, float *z0, float *z1)
     Cc = fmaf(Cc, w, 0x1.03c1eep-2f);
     Cc = fmaf(Cc, w, -0x1.3bd3ccp+0f);
     const float cs = fmaf(w, Cc, 1.0f);
-    /* z0 takes its sign from bit 8 of ra (the magnitude's own sign bit, which can be set by a rounding
+    /* z0 takes its sign from bit 31 of ra (the magnitude's own sign bit, which can be set by a rounding
      * error of cs at |x| = 1, is dropped) */
     const uint32_t mag = f32_as_u32(rho * cs) & 0x7FFFFFFFu;
-    *z0 = u32_as_f32(mag | ((ra << 23) & 0x80000000u));
+    *z0 = u32_as_f32(mag | (ra & 0x80000000u));
     *z1 = rho * sn;
 }
 

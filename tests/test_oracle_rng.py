@@ -47,22 +47,24 @@ def test_philox_fewer_rounds_differ():
 
 
 def _closed_form(ra, rb):
-    """The transform's definition, in fp64: u = (2 (ra >> 9) + 1) 2^-24, radius sqrt(-2 ln u); the angle is a quarter turn
-    times x, x = the fp32 nearest to rb read as a signed integer, times 2^-31; z1 = radius sin, z0 = -+radius cos with
-    the sign in bit 8 of ra."""
-    u = (2 * (ra >> 9) + 1) / 2.0**24
+    """The transform's definition, in fp64.  Radius: q = (2 j + 1) 2^-25 with j = bits 30..8 of ra; bit 4 of ra clear:
+    F = q, radius sqrt(-2 ln(1 - q)); set: 1 - F = q, radius sqrt(-2 ln q) (the Rayleigh quantile at F).  Angle: a quarter
+    turn times x, x = the fp32 nearest to rb read as a signed integer, times 2^-31.  z1 = radius sin, z0 = -+radius cos
+    with the sign in bit 31 of ra."""
+    q = (2 * ((ra >> 8) & 0x7FFFFF) + 1) / 2.0**25
+    rho = np.sqrt(-2.0 * np.log(q)) if (ra >> 4) & 1 else np.sqrt(-2.0 * np.log1p(-q))
     signed = rb - (1 << 32) if rb >= (1 << 31) else rb
     ang = float(np.float32(signed)) * 2.0**-31 * (np.pi / 2)
-    rho = np.sqrt(-2.0 * np.log(u))
-    return (-1.0 if (ra >> 8) & 1 else 1.0) * rho * np.cos(ang), rho * np.sin(ang)
+    return (-1.0 if ra >> 31 else 1.0) * rho * np.cos(ang), rho * np.sin(ang)
 
 
 def _closed_form_arrays(ra, rb):
     """The same over uint32 arrays."""
-    u = (2.0 * (ra >> np.uint32(9)).astype(np.float64) + 1.0) * 2.0**-24
+    q = (2.0 * ((ra >> np.uint32(8)) & np.uint32(0x7FFFFF)).astype(np.float64) + 1.0) * 2.0**-25
+    upper = ((ra >> np.uint32(4)) & np.uint32(1)) == 1
+    rho = np.where(upper, np.sqrt(-2.0 * np.log(q)), np.sqrt(-2.0 * np.log1p(-q)))
     ang = rb.view(np.int32).astype(np.float32).astype(np.float64) * 2.0**-31 * (np.pi / 2)
-    rho = np.sqrt(-2.0 * np.log(u))
-    sign = np.where((ra >> np.uint32(8)) & np.uint32(1), -1.0, 1.0)
+    sign = np.where(ra >> np.uint32(31), -1.0, 1.0)
     return sign * rho * np.cos(ang), rho * np.sin(ang), rho
 
 
@@ -81,10 +83,10 @@ def test_counter_layout_words_to_elements():
 
 def test_normal_pair_matches_closed_form_everywhere():
     rng = np.random.default_rng(11)
-    ras = list(rng.integers(0, 2**32, 20000)) + [0, 1 << 9, 0xFFFFFFFF, 0xFFFFFE00, 0x80000000, 0x7FFFFFFF, 0x100, 0xFFFFFEFF,
-                                                 0xFF800000, 0xFF7FFE00]
+    ras = list(rng.integers(0, 2**32, 20000)) + [0, 0x10, 0x100, 0x110, 0x7FFFFF00, 0x7FFFFF10, 0xFFFFFFFF, 0xFFFFFFEF, 0x80000000,
+                                                 0x80000010, 0x40000000, 0x3FFFFF10, 0x00000FFF, 0x000080FF]
     rbs = list(rng.integers(0, 2**32, 20000)) + [0, 0x7FFFFFFF, 0x80000000, 0xFFFFFFFF, 0x40000000, 0xC0000000, 1, 0x7FFFFF80,
-                                                 0x7FFFFFC0, 0x80000040]
+                                                 0x7FFFFFC0, 0x80000040, 0x01000001, 0xFEFFFFFF, 0x12345678, 0x9ABCDEF0]
     worst = 0.0
     for ra, rb in zip(ras, rbs):
         ra, rb = int(ra), int(rb)
@@ -96,10 +98,12 @@ def test_normal_pair_matches_closed_form_everywhere():
     assert worst < 4 * 2.0**-23, worst
 
 
-def test_every_radius_code_matches_closed_form():
-    """All 2^23 values of u (ra >> 9), both signs of the cosine: z0 = -+sqrt(-2 ln u) at angle 0, within 2 ulp."""
-    ra = np.arange(2**23, dtype=np.uint64).astype(np.uint32) << np.uint32(9)
-    ra |= (np.arange(2**23, dtype=np.uint32) & np.uint32(1)) << np.uint32(8)        # alternate the sign bit
+@pytest.mark.parametrize("upper", [0, 1])
+def test_every_radius_code_matches_closed_form(upper):
+    """All 2^23 values of q in either half of the distribution, the cosine's sign alternating: z0 = -+radius at angle
+    0, within 2 ulp of the Rayleigh quantile, and monotone in q (a wrong cell, pivot or coefficient breaks the order)."""
+    j = np.arange(2**23, dtype=np.uint32)
+    ra = (j << np.uint32(8)) | np.uint32(upper << 4) | ((j & np.uint32(1)) << np.uint32(31))
     words = np.empty(2 * ra.size, dtype=np.uint32)
     words[0::2] = ra
     words[1::2] = 0
@@ -109,16 +113,20 @@ def test_every_radius_code_matches_closed_form():
     assert np.all(np.signbit(z[0::2]) == (c0 < 0))
     err = np.abs(z[0::2].astype(np.float64) - c0) / np.spacing(rho.astype(np.float32)).astype(np.float64)
     assert err.max() < 2.0, (err.max(), int(err.argmax()))
-    # the radius shrinks as u grows: a wrong pivot or a swapped table entry would break the order somewhere
-    mag = np.abs(z[0::2])
-    assert np.all(mag[1:] <= mag[:-1]) and mag[0] == np.float32(np.sqrt(48 * np.log(2))) and mag[-1] > 0
+    mag = np.abs(z[0::2]).astype(np.float64)
+    if upper:
+        assert np.all(mag[1:] <= mag[:-1]) and abs(mag[0] - np.sqrt(50 * np.log(2))) < 1e-6      # q = 2^-25
+        assert abs(mag[-1] - np.sqrt(2 * np.log(2))) < 1e-6                                       # the median, from above
+    else:
+        assert np.all(mag[1:] >= mag[:-1]) and abs(mag[0] / np.sqrt(2.0**-24) - 1) < 1e-6         # sqrt(-2 ln(1 - 2^-25))
+        assert abs(mag[-1] - np.sqrt(2 * np.log(2))) < 1e-6                                       # the median, from below
 
 
 def test_every_angle_code_matches_closed_form():
     """All 2^24 angles rb = i << 8 (every value of the top 24 bits, both signs) at a fixed radius: absolute error of
     (cos, sin) within 3 fp32 ulps of 1, and cos^2 + sin^2 = 1."""
     rb = np.arange(2**24, dtype=np.uint64).astype(np.uint32) << np.uint32(8)
-    ra = np.full(rb.size, 0x9B17A400, dtype=np.uint32)             # u = 0.6058..., radius about 1
+    ra = np.full(rb.size, 0x64E85C00, dtype=np.uint32)             # F = 0.394..., radius about 1
     words = np.empty(2 * rb.size, dtype=np.uint32)
     words[0::2] = ra
     words[1::2] = rb
@@ -131,26 +139,30 @@ def test_every_angle_code_matches_closed_form():
 
 
 def test_normal_radius_identity_and_extremes():
-    # z0^2 + z1^2 = -2 ln u, largest radius at u = 2^-24, smallest at u = 1 - 2^-24
-    for ra, rb in [(0, 0x12345678), (0xFFFFFFFF, 0x9ABCDEF0), (0x40000000, 0)]:
+    # z0^2 + z1^2 = radius^2 = -2 ln(1 - F); the largest radius at 1 - F = 2^-25, the smallest at F = 2^-25
+    for ra, rb in [(0, 0x12345678), (0xFFFFFFFF, 0x9ABCDEF0), (0x40000010, 0), (0x12345678, 0x40000000)]:
         z0, z1 = zo.normal_pair(ra, rb)
-        u = (2 * (ra >> 9) + 1) / 2.0**24
-        assert abs((float(z0)**2 + float(z1)**2) / (-2 * np.log(u)) - 1) < 1e-6
+        q = (2 * ((ra >> 8) & 0x7FFFFF) + 1) / 2.0**25
+        f = 1 - q if (ra >> 4) & 1 else q
+        assert abs((float(z0)**2 + float(z1)**2) / (-2 * np.log1p(-f)) - 1) < 1e-6
+    s = float(np.sqrt(50 * np.log(2)))
+    z0, z1 = zo.normal_pair(0x10, 0)
+    assert abs(float(z0) - s) < 1e-5 and z1 == 0
     z0, z1 = zo.normal_pair(0, 0)
-    assert abs(float(z0) - np.sqrt(2 * 24 * np.log(2))) < 1e-5 and z1 == 0
-    z0, z1 = zo.normal_pair(0xFFFFFE00, 0)
-    assert abs(float(z0) / np.sqrt(-2 * np.log1p(-2.0**-24)) - 1) < 1e-6
-    # directions: angle 0 is the +-z0 axis (sign in bit 8 of ra), a quarter turn either way the +-z1 axis, and the
+    assert abs(float(z0) / np.sqrt(-2 * np.log1p(-2.0**-25)) - 1) < 1e-6
+    # the two halves meet at the median of the radius, sqrt(2 ln 2)
+    lo, hi = float(zo.normal_pair(0x7FFFFF00, 0)[0]), float(zo.normal_pair(0x7FFFFF10, 0)[0])
+    assert lo < np.sqrt(2 * np.log(2)) < hi and hi - lo < 1e-6
+    # directions: angle 0 is the +-z0 axis (sign in bit 31 of ra), a quarter turn either way the +-z1 axis, and the
     # four sign combinations at an eighth of a turn land in the four quadrants
-    s = float(np.sqrt(2 * 24 * np.log(2)))
-    assert [float(v) for v in zo.normal_pair(0x100, 0)] == [-float(np.float32(s)), 0.0]
-    z0, z1 = zo.normal_pair(0, 0x7FFFFFFF)
+    assert [float(v) for v in zo.normal_pair(0x80000010, 0)] == [-float(np.float32(s)), 0.0]
+    z0, z1 = zo.normal_pair(0x10, 0x7FFFFFFF)
     assert abs(float(z1) - s) < 1e-5 and abs(float(z0)) < 1e-6
-    z0, z1 = zo.normal_pair(0, 0x80000000)
+    z0, z1 = zo.normal_pair(0x10, 0x80000000)
     assert abs(float(z1) + s) < 1e-5 and abs(float(z0)) < 1e-6
-    quads = [np.sign(zo.normal_pair(ra, rb)).tolist() for ra in (0, 0x100) for rb in (0x40000000, 0xC0000000)]
+    quads = [np.sign(zo.normal_pair(ra, rb)).tolist() for ra in (0x10, 0x80000010) for rb in (0x40000000, 0xC0000000)]
     assert quads == [[1, 1], [1, -1], [-1, 1], [-1, -1]]
-    z0, z1 = zo.normal_pair(0, 0x40000000)
+    z0, z1 = zo.normal_pair(0x10, 0x40000000)
     assert abs(float(z0) - s / np.sqrt(2)) < 1e-5 and abs(float(z1) - s / np.sqrt(2)) < 1e-5
 
 
