@@ -15,7 +15,10 @@ struct TensorDesc {          // one tensor of an in-place pass
     uint32_t tid;
     uint32_t pad;
 };
-constexpr uint32_t kAxpyChunk = 4096;   // elements per workgroup
+#ifndef ZO_AXPY_CHUNK
+#define ZO_AXPY_CHUNK 8192
+#endif
+constexpr uint32_t kAxpyChunk = ZO_AXPY_CHUNK;   // elements per chunk (one workgroup iteration)
 
 struct StageDesc {           // one tensor of an out-of-place W+- staging pass
     const void *src;

@@ -5,14 +5,14 @@
 // (s, t, i), so "reset the generator to seed s" costs nothing and any kernel can regenerate
 // exactly the values another one used.  Generator: Philox4x32-10 (Salmon et al., SC'11), one
 // block per four consecutive elements.  Transform: pair-wise Box-Muller whose fp32 arithmetic
-// is fixed operation by operation (only IEEE conversions, mul, fma, sqrt, integer ops and one
-// lookup in a 512-entry table of fp32 constants), so the bits are the same on any IEEE-754
-// machine.  Must be compiled with -ffp-contract=off.
+// is fixed operation by operation (only IEEE conversions, add, mul, fma, integer ops and one
+// lookup in a table of fp32 constants), so the bits are the same on any IEEE-754 machine.
+// Must be compiled with -ffp-contract=off.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "zo_ln_table.hip.h"
+#include "zo_rayleigh_table.hip.h"
 
 namespace zo {
 
@@ -70,55 +70,36 @@ __device__ __forceinline__ u32x4 philox_block(uint64_t seed, uint32_t tid, uint6
     return philox4x32_10((uint32_t)j, (uint32_t)(j >> 32), tid, tag, (uint32_t)seed, (uint32_t)(seed >> 32));
 }
 
-// Correctly rounded square root for the arguments the radius takes (t = -2 ln u with u = k 2^-24, k odd: 1.19e-7
-// <= t <= 33.3, so no scaling for subnormals or huge values is needed, which is what makes the compiler's
-// general sequence long): reciprocal square root estimate y, one Newton step for g = sqrt(t), and a final
-// correction from the exact residual t - g^2 with the unrefined y/2 as 1/(2 sqrt(t)) (its error is far below
-// what the correction can see).  Checked against the IEEE result for every one of the 2^23 arguments that can
-// occur.
-__device__ __forceinline__ float sqrt_rn(float t)
+// The radius table in LDS.  `tab` is a virtual base: entries [kRayleighFirst, kRayleighLast) of it must be LDS that
+// the workgroup owns (24 KiB); the entries below kRayleighFirst are never touched, so a kernel with other LDS data
+// puts those in front of the table.  Every kernel that draws normals fills the table once per workgroup and
+// synchronises before the first draw; workgroups are persistent so that this is paid once per CU slot and launch.
+__device__ __forceinline__ void load_rayleigh_cells(float4 *tab)
 {
-    const float y = __builtin_amdgcn_rsqf(t);
-    float g = t * y;
-    const float h = 0.5f * y;
-    const float r = __builtin_fmaf(-h, g, 0.5f);
-    g = __builtin_fmaf(g, r, g);
-    const float d = __builtin_fmaf(-g, g, t);
-    return __builtin_fmaf(d, h, g);
-}
-
-// The logarithm's pivot table in LDS: 512 {inv_i, l_i} pairs, 4 KiB.  Every kernel that draws normals copies it
-// from constant memory once per workgroup (256 threads x 16 bytes) and synchronises before the first draw.
-constexpr int kLnPivots = 512;
-__device__ __forceinline__ void load_ln_pivots(float2 *tab /* LDS, kLnPivots entries */)
-{
-    for (int i = threadIdx.x; i < kLnPivots / 2; i += blockDim.x)
-        ((float4 *)tab)[i] = ((const float4 *)kLnPivot)[i];
+    for (int i = kRayleighFirst + (int)threadIdx.x; i < kRayleighLast; i += (int)blockDim.x) tab[i] = kRayleighCell[i];
     __syncthreads();
 }
 
 // Two standard normals from two words.
-//   radius  u = (2 (ra >> 9) + 1) 2^-24 in (0,1), rho = sqrt(-2 ln u)
+//   radius  Rayleigh-distributed, by inversion: q = (2 j + 1) 2^-25 in (0, 1/2), j = bits 30..8 of ra; bit 4 of ra
+//           clear: F = q, rho = sqrt(-2 ln(1 - q)); set: 1 - F = q, rho = sqrt(-2 ln q)
 //   angle   x = (float)(int32)rb 2^-31 in [-1, 1], a quarter turn either way
-//   z1 = rho sin(pi x / 2);  z0 = -+rho cos(pi x / 2), negative when bit 8 of ra is set.
-// The logarithm: uf = (float)(k 2^8) (exact) has the biased exponent E; u = m 4^n with n = (E >> 1) - 79 and m, the
-// significand of uf under the exponent 126 + (E & 1), in [0.5, 2).  Bits 23..15 of uf select one of 512 significand
-// intervals with pivot p_i (its midpoint; 1 for the interval that ends at m = 1); r = m inv_i - 1 is at most 2^-9 and
-//   -2 ln u = n (-4 ln 2) + l_i + r (-2 + r (1 - (2/3) r))
-// with {inv_i, l_i} = {fl(1 / p_i), fl(2 ln inv_i)} from the table.  A table lookup and three fused multiply-adds
-// take the place of a ten-term logarithm polynomial; sign bits take the place of quadrant logic.
-__device__ __forceinline__ void normal_pair(uint32_t ra, uint32_t rb, float &z0, float &z1, const float2 *tab)
+//   z1 = rho sin(pi x / 2);  z0 = -+rho cos(pi x / 2), negative when bit 31 of ra is set.
+// Neither logarithm nor square root is evaluated: both halves of the quantile are smooth in the relative position
+// of q inside a binade, so qf = (float)((2 j + 1) 2^7) (exact) picks a cell by its exponent and top five fraction
+// bits, and rho = a0 + d (a1 + d (a2 + d a3)) with d = qf - (the cell's midpoint), exact, and a_k the fp32 Taylor
+// coefficients from the table.  Ten instructions for the radius: and-or, convert, and-or, subtract, three for the
+// table address, three fused multiply-adds.
+__device__ __forceinline__ void normal_pair(uint32_t ra, uint32_t rb, float &z0, float &z1, const float4 *tab)
 {
-    const float uf = (float)and_or(ra, 0xFFFFFE00u, 0x100u);
-    const uint32_t b = __float_as_uint(uf);
-    const float nf = (float)(b >> 24) - 79.0f;
-    const float m = __uint_as_float((b & 0x00FFFFFFu) | 0x3F000000u);
-    const float2 pv = tab[(b >> 15) & 0x1FFu];
-    const float r = __builtin_fmaf(m, pv.x, -1.0f);
-    const float base = __builtin_fmaf(nf, -0x1.62e430p+1f, pv.y);
-    float p = __builtin_fmaf(r, -0x1.555556p-1f, 1.0f);
-    p = __builtin_fmaf(p, r, -2.0f);
-    const float rho = sqrt_rn(__builtin_fmaf(r, p, base));
+    const float qf = (float)and_or(ra, 0x7FFFFF00u, 0x80u);
+    const uint32_t b = __float_as_uint(qf);
+    const float d = qf - __uint_as_float(and_or(b, 0xFFFC0000u, 0x00020000u));
+    // entry 2 c + h, c = (b >> 18) mod 1024, 16 bytes each: byte offset ((b >> 13) & 0x7FE0) | (ra & 0x10)
+    const float4 a = *(const float4 *)((const char *)tab + and_or(b >> 13, 0x7FE0u, ra & 0x10u));
+    float rho = __builtin_fmaf(a.w, d, a.z);
+    rho = __builtin_fmaf(rho, d, a.y);
+    rho = __builtin_fmaf(rho, d, a.x);
 
     const float x = (float)(int32_t)rb * 0x1p-31f;
     const float w = x * x;
@@ -134,11 +115,11 @@ __device__ __forceinline__ void normal_pair(uint32_t ra, uint32_t rb, float &z0,
     cp = __builtin_fmaf(cp, w, -0x1.3bd3ccp+0f);
     const float cs = __builtin_fmaf(w, cp, 1.0f);
     z1 = rho * (x * sp);
-    // magnitude of rho cos with the sign taken from bit 8 of ra (one bit-field insert)
-    z0 = __uint_as_float(bit_select(0x7FFFFFFFu, __float_as_uint(rho * cs), ra << 23));
+    // magnitude of rho cos with the sign bit of ra (one bit-field insert)
+    z0 = __uint_as_float(bit_select(0x7FFFFFFFu, __float_as_uint(rho * cs), ra));
 }
 
-__device__ __forceinline__ void normal4(const u32x4 &wd, float z[4], const float2 *tab)
+__device__ __forceinline__ void normal4(const u32x4 &wd, float z[4], const float4 *tab)
 {
     normal_pair(wd.x, wd.y, z[0], z[1], tab);
     normal_pair(wd.z, wd.w, z[2], z[3], tab);

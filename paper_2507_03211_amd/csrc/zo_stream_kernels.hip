@@ -2,8 +2,10 @@
 // Eq. 2) and the out-of-place staging of W+- = rn(theta +- eps z) (PertP workflow, Step 2).
 //
 // All of them are one pass over the parameters with z regenerated in registers from its
-// counter: 16-byte coalesced loads and stores, four independent Philox blocks per thread for
-// instruction-level parallelism, no LDS except for the transposing stage.
+// counter: 16-byte coalesced loads and stores, independent Philox blocks per thread for
+// instruction-level parallelism.  The normal transform reads its radius from a 24 KiB table in
+// LDS, so the workgroups are persistent: a few per CU, each filling the table once and then
+// walking chunks (tiles) blockIdx.x, blockIdx.x + gridDim.x, ...
 #include <type_traits>
 
 #include "zo_kernels.h"
@@ -15,8 +17,8 @@ namespace zo {
 // ------------------------------------------------------------------ z only (verification)
 __global__ __launch_bounds__(256) void z_kernel(float *out, uint64_t n, uint64_t seed, uint32_t tid, uint64_t first)
 {
-    __shared__ float2 ln_tab[kLnPivots];
-    load_ln_pivots(ln_tab);
+    __shared__ float4 ln_tab[kRayleighLast];
+    load_rayleigh_cells(ln_tab);
     // one Philox block per thread; blocks first/4 .. (first+n-1)/4
     const uint64_t j = first / 4 + (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (4 * j >= first + n) return;
@@ -31,8 +33,8 @@ __global__ __launch_bounds__(256) void z_kernel(float *out, uint64_t n, uint64_t
 
 __global__ __launch_bounds__(256) void normal_pairs_kernel(const uint32_t *words, float *z, uint64_t n_pairs)
 {
-    __shared__ float2 ln_tab[kLnPivots];
-    load_ln_pivots(ln_tab);
+    __shared__ float4 ln_tab[kRayleighLast];
+    load_rayleigh_cells(ln_tab);
     const uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= n_pairs) return;
     float a, b;
@@ -95,92 +97,131 @@ template <int DT> __device__ __forceinline__ uint4 pack16(const float *f)
     }
 }
 
-// One workgroup = one chunk of kAxpyChunk elements of one tensor.  SR: stochastic instead of nearest
-// rounding into the storage type, with the random word of element i taken from word i % 4 of the
-// Philox block (i / 4, tensor, tag 3) under the same seed.
+// One chunk = kAxpyChunk consecutive elements of one tensor; workgroup w of a launch takes chunks w, w + gridDim.x, ...
+// of the launch's `total_chunks`.  SR: stochastic instead of nearest rounding into the storage type, with the random
+// word of element i taken from word i % 4 of the Philox block (i / 4, tensor, tag 3) under the same seed.
+#ifndef ZO_STREAM_THREADS
+#define ZO_STREAM_THREADS 512
+#endif
+#ifndef ZO_AXPY_PER_CU
+#define ZO_AXPY_PER_CU 4
+#endif
+constexpr int kStreamThreads = ZO_STREAM_THREADS;      // 4 workgroups of 8 waves fill a CU's 32 wave slots; 30 KiB of LDS each
 template <int DT, bool SR>
-__global__ __launch_bounds__(256) void axpy_z_kernel(const TensorDesc *__restrict__ descs, int n_desc, TensorDesc single,
-                                                     uint64_t chunk_offset, uint64_t seed, float scale,
-                                                     const float *__restrict__ dev_scale)
+__global__ __launch_bounds__(kStreamThreads) void axpy_z_kernel(const TensorDesc *__restrict__ descs, int n_desc, TensorDesc single,
+                                                                uint64_t chunk_offset, uint32_t total_chunks, uint64_t seed, float scale,
+                                                                const float *__restrict__ dev_scale)
 {
     using W = typename Prec<DT>::W;
     constexpr int VN = Vec16<DT>::N;
-    __shared__ float2 ln_tab[kLnPivots];
-    load_ln_pivots(ln_tab);
-    TensorDesc d;
-    const uint64_t chunk = (uint64_t)blockIdx.x + chunk_offset;
+    constexpr int kIter = kAxpyChunk / (kStreamThreads * VN);
+    static_assert(kIter >= 1 && kIter * kStreamThreads * VN == (int)kAxpyChunk, "a chunk is a whole number of 16-byte pieces per thread");
+    __shared__ float4 ln_tab[kRayleighLast];
+    load_rayleigh_cells(ln_tab);
+    const float sc = dev_scale ? *dev_scale : scale;
+    int di = 0;
     if (descs) {
-        // last descriptor whose first_chunk <= chunk
+        // last descriptor whose first_chunk <= this workgroup's first chunk; later chunks only ever move forward from it
+        const uint64_t chunk = (uint64_t)blockIdx.x + chunk_offset;
         int lo = 0, hi = n_desc - 1;
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
             if (descs[mid].first_chunk <= chunk) lo = mid; else hi = mid - 1;
         }
-        d = descs[lo];
-    } else {
-        d = single;
+        di = lo;
     }
-    const float sc = dev_scale ? *dev_scale : scale;
-    const uint64_t base = (chunk - d.first_chunk) * kAxpyChunk;
-    const W *__restrict__ src = (const W *)d.src;
-    W *__restrict__ dst = (W *)d.dst;
-    constexpr int kIter = kAxpyChunk / (256 * VN);
-    if (base + kAxpyChunk <= d.numel) {
-        // a chunk that lies wholly inside its tensor (all but a tensor's last): no bounds logic between the
-        // iterations, so the compiler schedules them as one body and sets the generator's constants up once
+    auto desc_of = [&](uint64_t chunk) {
+        if (!descs) return single;
+        while (di + 1 < n_desc && descs[di + 1].first_chunk <= chunk) ++di;
+        return descs[di];
+    };
+    // A chunk that lies wholly inside its tensor (all but a tensor's last) is loaded one iteration ahead, into
+    // registers, so that a wave never waits for memory with nothing to compute; the others take the guarded path.
+    auto whole_chunk = [&](const TensorDesc &d, uint64_t chunk) { return ((chunk - d.first_chunk) + 1) * kAxpyChunk <= d.numel; };
+    auto load_chunk = [&](const TensorDesc &d, uint64_t chunk, uint4 (&v)[kIter]) {
+        const W *__restrict__ src = (const W *)d.src + (chunk - d.first_chunk) * kAxpyChunk;
 #pragma unroll
-        for (int it = 0; it < kIter; ++it) {
-            const uint64_t i0 = base + (uint64_t)(it * 256 + threadIdx.x) * VN;
-            float z[VN];
+        for (int it = 0; it < kIter; ++it) v[it] = *(const uint4 *)(src + (size_t)(it * kStreamThreads + threadIdx.x) * VN);
+    };
+    uint32_t c = blockIdx.x;
+    if (c >= total_chunks) return;
+    TensorDesc d = desc_of((uint64_t)c + chunk_offset);
+    bool whole = whole_chunk(d, (uint64_t)c + chunk_offset);
+    uint4 cur[kIter], nxt[kIter];
+    if (whole) load_chunk(d, (uint64_t)c + chunk_offset, cur);
+    for (;;) {
+        const uint64_t chunk = (uint64_t)c + chunk_offset;
+        const uint32_t cn = c + gridDim.x;
+        const bool has_next = cn < total_chunks;
+        TensorDesc dn = d;
+        bool whole_n = false;
+        if (has_next) {
+            dn = desc_of((uint64_t)cn + chunk_offset);
+            whole_n = whole_chunk(dn, (uint64_t)cn + chunk_offset);
+            if (whole_n) load_chunk(dn, (uint64_t)cn + chunk_offset, nxt);
+        }
+        const uint64_t base = (chunk - d.first_chunk) * kAxpyChunk;
+        const W *__restrict__ src = (const W *)d.src;
+        W *__restrict__ dst = (W *)d.dst;
+        if (whole) {
 #pragma unroll
-            for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
-            float th[VN];
-            unpack16<DT>(*(const uint4 *)(src + i0), th);
+            for (int it = 0; it < kIter; ++it) {
+                const uint64_t i0 = base + (uint64_t)(it * kStreamThreads + threadIdx.x) * VN;
+                float z[VN];
 #pragma unroll
-            for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
-            if constexpr (SR) {
-                uint32_t rw[VN];
+                for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
+                float th[VN];
+                unpack16<DT>(cur[it], th);
 #pragma unroll
-                for (int b = 0; b < VN / 4; ++b) {
-                    const u32x4 r = philox_block(seed, d.tid, i0 / 4 + b, 3u);
-                    rw[4 * b] = r.x; rw[4 * b + 1] = r.y; rw[4 * b + 2] = r.z; rw[4 * b + 3] = r.w;
+                for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
+                if constexpr (SR) {
+                    uint32_t rw[VN];
+#pragma unroll
+                    for (int b = 0; b < VN / 4; ++b) {
+                        const u32x4 r = philox_block(seed, d.tid, i0 / 4 + b, 3u);
+                        rw[4 * b] = r.x; rw[4 * b + 1] = r.y; rw[4 * b + 2] = r.z; rw[4 * b + 3] = r.w;
+                    }
+                    *(uint4 *)(dst + i0) = pack16_sr<DT>(th, rw);
+                } else {
+                    *(uint4 *)(dst + i0) = pack16<DT>(th);
                 }
-                *(uint4 *)(dst + i0) = pack16_sr<DT>(th, rw);
-            } else {
-                *(uint4 *)(dst + i0) = pack16<DT>(th);
             }
-        }
-        return;
-    }
-#pragma unroll
-    for (int it = 0; it < kIter; ++it) {
-        const uint64_t i0 = base + (uint64_t)(it * 256 + threadIdx.x) * VN;
-        if (i0 >= d.numel) break;
-        float z[VN];
-#pragma unroll
-        for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
-        uint32_t rw[SR ? VN : 1];
-        if constexpr (SR) {
-#pragma unroll
-            for (int b = 0; b < VN / 4; ++b) {
-                const u32x4 r = philox_block(seed, d.tid, i0 / 4 + b, 3u);
-                rw[4 * b] = r.x; rw[4 * b + 1] = r.y; rw[4 * b + 2] = r.z; rw[4 * b + 3] = r.w;
-            }
-        }
-        if (i0 + VN <= d.numel) {
-            float th[VN];
-            unpack16<DT>(*(const uint4 *)(src + i0), th);
-#pragma unroll
-            for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
-            if constexpr (SR) *(uint4 *)(dst + i0) = pack16_sr<DT>(th, rw);
-            else *(uint4 *)(dst + i0) = pack16<DT>(th);
         } else {
-            for (int e = 0; e < VN && i0 + e < d.numel; ++e) {
-                const float v = __builtin_fmaf(sc, z[e], Prec<DT>::w2f(src[i0 + e]));
-                if constexpr (SR) dst[i0 + e] = DT == kBF16 ? sr_to_bf16(v, rw[e]) : sr_to_f16(v, rw[e]);
-                else dst[i0 + e] = Prec<DT>::f2w(v);
+#pragma unroll 1
+            for (int it = 0; it < kIter; ++it) {
+                const uint64_t i0 = base + (uint64_t)(it * kStreamThreads + threadIdx.x) * VN;
+                if (i0 >= d.numel) break;
+                float z[VN];
+#pragma unroll
+                for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
+                uint32_t rw[SR ? VN : 1];
+                if constexpr (SR) {
+#pragma unroll
+                    for (int b = 0; b < VN / 4; ++b) {
+                        const u32x4 r = philox_block(seed, d.tid, i0 / 4 + b, 3u);
+                        rw[4 * b] = r.x; rw[4 * b + 1] = r.y; rw[4 * b + 2] = r.z; rw[4 * b + 3] = r.w;
+                    }
+                }
+                if (i0 + VN <= d.numel) {
+                    float th[VN];
+                    unpack16<DT>(*(const uint4 *)(src + i0), th);
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
+                    if constexpr (SR) *(uint4 *)(dst + i0) = pack16_sr<DT>(th, rw);
+                    else *(uint4 *)(dst + i0) = pack16<DT>(th);
+                } else {
+                    for (int e = 0; e < VN && i0 + e < d.numel; ++e) {
+                        const float v = __builtin_fmaf(sc, z[e], Prec<DT>::w2f(src[i0 + e]));
+                        if constexpr (SR) dst[i0 + e] = DT == kBF16 ? sr_to_bf16(v, rw[e]) : sr_to_f16(v, rw[e]);
+                        else dst[i0 + e] = Prec<DT>::f2w(v);
+                    }
+                }
             }
         }
+        if (!has_next) break;
+        c = cn; d = dn; whole = whole_n;
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) cur[it] = nxt[it];
     }
 }
 
@@ -189,61 +230,70 @@ __global__ __launch_bounds__(256) void axpy_z_kernel(const TensorDesc *__restric
 // storage type before the next starts from it, exactly as n separate passes would leave it, with one read and
 // one write of theta.  Same chunking and addressing as axpy_z_kernel; the scalars are dev_scale[0 .. n-1].
 template <int DT, bool SR>
-__global__ __launch_bounds__(256) void axpy_z_multi_kernel(const TensorDesc *__restrict__ descs, int n_desc, uint64_t chunk_offset,
-                                                           UpdateSeeds upd, const float *__restrict__ dev_scale)
+__global__ __launch_bounds__(kStreamThreads) void axpy_z_multi_kernel(const TensorDesc *__restrict__ descs, int n_desc,
+                                                                      uint64_t chunk_offset, uint32_t total_chunks, UpdateSeeds upd,
+                                                                      const float *__restrict__ dev_scale)
 {
     using W = typename Prec<DT>::W;
     constexpr int VN = Vec16<DT>::N;
-    __shared__ float2 ln_tab[kLnPivots];
-    load_ln_pivots(ln_tab);
-    const uint64_t chunk = (uint64_t)blockIdx.x + chunk_offset;
-    int lo = 0, hi = n_desc - 1;                      // last descriptor whose first_chunk <= chunk
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (descs[mid].first_chunk <= chunk) lo = mid; else hi = mid - 1;
+    __shared__ float4 ln_tab[kRayleighLast];
+    load_rayleigh_cells(ln_tab);
+    int di;
+    {
+        const uint64_t chunk = (uint64_t)blockIdx.x + chunk_offset;
+        int lo = 0, hi = n_desc - 1;                      // last descriptor whose first_chunk <= chunk
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (descs[mid].first_chunk <= chunk) lo = mid; else hi = mid - 1;
+        }
+        di = lo;
     }
-    const TensorDesc d = descs[lo];
-    const uint64_t base = (chunk - d.first_chunk) * kAxpyChunk;
-    const W *__restrict__ src = (const W *)d.src;
-    W *__restrict__ dst = (W *)d.dst;
-    constexpr int kIter = kAxpyChunk / (256 * VN);
+    for (uint32_t c = blockIdx.x; c < total_chunks; c += gridDim.x) {
+        const uint64_t chunk = (uint64_t)c + chunk_offset;
+        while (di + 1 < n_desc && descs[di + 1].first_chunk <= chunk) ++di;
+        const TensorDesc d = descs[di];
+        const uint64_t base = (chunk - d.first_chunk) * kAxpyChunk;
+        const W *__restrict__ src = (const W *)d.src;
+        W *__restrict__ dst = (W *)d.dst;
+        constexpr int kIter = kAxpyChunk / (kStreamThreads * VN);
 #pragma unroll
-    for (int it = 0; it < kIter; ++it) {
-        const uint64_t i0 = base + (uint64_t)(it * 256 + threadIdx.x) * VN;
-        if (i0 >= d.numel) break;
-        const bool whole = i0 + VN <= d.numel;
-        float th[VN];
-        if (whole) {
-            unpack16<DT>(*(const uint4 *)(src + i0), th);
-        } else {
-            for (int e = 0; e < VN; ++e) th[e] = i0 + e < d.numel ? Prec<DT>::w2f(src[i0 + e]) : 0.0f;
-        }
-        uint4 packed = uint4{0u, 0u, 0u, 0u};
-        for (int j = 0; j < upd.n; ++j) {
-            const uint64_t seed = upd.seed[j];
-            const float sc = dev_scale[j];
-            float z[VN];
-#pragma unroll
-            for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
-#pragma unroll
-            for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
-            if constexpr (SR) {
-                uint32_t rw[VN];
-#pragma unroll
-                for (int b = 0; b < VN / 4; ++b) {
-                    const u32x4 r = philox_block(seed, d.tid, i0 / 4 + b, 3u);
-                    rw[4 * b] = r.x; rw[4 * b + 1] = r.y; rw[4 * b + 2] = r.z; rw[4 * b + 3] = r.w;
-                }
-                packed = pack16_sr<DT>(th, rw);
+        for (int it = 0; it < kIter; ++it) {
+            const uint64_t i0 = base + (uint64_t)(it * kStreamThreads + threadIdx.x) * VN;
+            if (i0 >= d.numel) break;
+            const bool whole = i0 + VN <= d.numel;
+            float th[VN];
+            if (whole) {
+                unpack16<DT>(*(const uint4 *)(src + i0), th);
             } else {
-                packed = pack16<DT>(th);
+                for (int e = 0; e < VN; ++e) th[e] = i0 + e < d.numel ? Prec<DT>::w2f(src[i0 + e]) : 0.0f;
             }
-            unpack16<DT>(packed, th);                 // the next update starts from the stored value
-        }
-        if (whole) {
-            *(uint4 *)(dst + i0) = packed;
-        } else {
-            for (int e = 0; e < VN && i0 + e < d.numel; ++e) dst[i0 + e] = Prec<DT>::f2w(th[e]);   // exact: th holds stored values
+            uint4 packed = uint4{0u, 0u, 0u, 0u};
+            for (int j = 0; j < upd.n; ++j) {
+                const uint64_t seed = upd.seed[j];
+                const float sc = dev_scale[j];
+                float z[VN];
+#pragma unroll
+                for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(sc, z[e], th[e]);
+                if constexpr (SR) {
+                    uint32_t rw[VN];
+#pragma unroll
+                    for (int b = 0; b < VN / 4; ++b) {
+                        const u32x4 r = philox_block(seed, d.tid, i0 / 4 + b, 3u);
+                        rw[4 * b] = r.x; rw[4 * b + 1] = r.y; rw[4 * b + 2] = r.z; rw[4 * b + 3] = r.w;
+                    }
+                    packed = pack16_sr<DT>(th, rw);
+                } else {
+                    packed = pack16<DT>(th);
+                }
+                unpack16<DT>(packed, th);                 // the next update starts from the stored value
+            }
+            if (whole) {
+                *(uint4 *)(dst + i0) = packed;
+            } else {
+                for (int e = 0; e < VN && i0 + e < d.numel; ++e) dst[i0 + e] = Prec<DT>::f2w(th[e]);   // exact: th holds stored values
+            }
         }
     }
 }
@@ -256,199 +306,242 @@ __global__ __launch_bounds__(256) void axpy_z_multi_kernel(const TensorDesc *__r
 // drawn from `upd_seed` and s read from dev_scale (UPD 1: round to nearest, 2: stochastic rounding), writes theta
 // back, and stages W+- from the updated value: Alg. 2's deferred update, in the pass that reads theta anyway.  The
 // arithmetic per element is that of axpy_z_kernel followed by the plain staging.
+#ifndef ZO_STAGE_THREADS
+#define ZO_STAGE_THREADS 1024
+#endif
+#ifndef ZO_STAGE_PER_CU
+#define ZO_STAGE_PER_CU 2
+#endif
+constexpr int kStageThreads = ZO_STAGE_THREADS;       // groups of 256 threads, one tile each
+// A workgroup is kStageThreads / 256 groups of 256 threads that share the radius table; in every round of the
+// persistent loop each group takes one tile (group g of workgroup w: tiles (w + i gridDim.x) G + g).  A transposing
+// tile goes through the group's LDS buffer one sign at a time (W+ out, then W-), which halves the buffer and lets
+// two 1024-thread workgroups, all 32 wave slots, share a CU next to the 24 KiB table.  The barriers of a round are
+// the same for every group whatever its tile is (flat, transposing or none).
 template <int DT, bool SINGLE, int UPD>
-__global__ __launch_bounds__(256) void stage_kernel(StageBatch batch, uint64_t seed, float eps, uint64_t upd_seed,
-                                                    const float *__restrict__ dev_scale)
+__global__ __launch_bounds__(kStageThreads) void stage_kernel(StageBatch batch, uint64_t seed, float eps, uint64_t upd_seed,
+                                                              const float *__restrict__ dev_scale)
 {
     using W = typename Prec<DT>::W;
     constexpr int VN = Vec16<DT>::N;
     static_assert(!(SINGLE && UPD != 0) && !(DT == kFP32 && UPD == 2), "no such variant");
-    __shared__ float2 ln_tab[SINGLE ? 1 : kLnPivots];
-    if constexpr (!SINGLE) load_ln_pivots(ln_tab);
-    float us = 0.0f;
-    if constexpr (UPD != 0) us = *dev_scale;
-    int di = 0;
-    for (int i = 1; i < batch.n; ++i)
-        if (batch.d[i].first_tile <= blockIdx.x) di = i;
-    const StageDesc &d = batch.d[di];
-    const uint32_t tile = blockIdx.x - d.first_tile;
-    W *const theta = (W *)const_cast<void *>(d.src);      // written only when UPD != 0
-    const W *src = theta;
-    W *__restrict__ dp = (W *)d.dst_plus;
-    W *__restrict__ dm = (W *)d.dst_minus;
-    const uint64_t numel = (uint64_t)d.rows * d.cols;
-
-    if (!d.transpose) {
-        constexpr int kIter = kStageFlatTile / (256 * VN);
-#pragma unroll
-        for (int it = 0; it < kIter; ++it) {
-            const uint64_t i0 = (uint64_t)tile * kStageFlatTile + (uint64_t)(it * 256 + threadIdx.x) * VN;
-            if (i0 >= numel) break;
-            float z[VN];
-            if constexpr (!SINGLE) {
-#pragma unroll
-                for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
-            }
-            const bool whole = i0 + VN <= numel;
-            if constexpr (SINGLE) {
-                if (whole) *(uint4 *)(dp + i0) = *(const uint4 *)(src + i0);
-                else for (int e = 0; e < VN && i0 + e < numel; ++e) dp[i0 + e] = src[i0 + e];
-            } else {
-                float th[VN], a[VN], b[VN];
-                if (whole) {
-                    unpack16<DT>(*(const uint4 *)(src + i0), th);
-                } else {
-                    for (int e = 0; e < VN; ++e) th[e] = i0 + e < numel ? Prec<DT>::w2f(src[i0 + e]) : 0.0f;
-                }
-                if constexpr (UPD != 0) {
-                    float zu[VN];
-#pragma unroll
-                    for (int bk = 0; bk < VN / 4; ++bk) normal4(philox_block(upd_seed, d.tid, i0 / 4 + bk), zu + 4 * bk, ln_tab);
-#pragma unroll
-                    for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(us, zu[e], th[e]);
-                    uint4 stored;
-                    if constexpr (UPD == 2) {
-                        uint32_t rw[VN];
-#pragma unroll
-                        for (int bk = 0; bk < VN / 4; ++bk) {
-                            const u32x4 r = philox_block(upd_seed, d.tid, i0 / 4 + bk, 3u);
-                            rw[4 * bk] = r.x; rw[4 * bk + 1] = r.y; rw[4 * bk + 2] = r.z; rw[4 * bk + 3] = r.w;
-                        }
-                        stored = pack16_sr<DT>(th, rw);
-                    } else {
-                        stored = pack16<DT>(th);
-                    }
-                    unpack16<DT>(stored, th);          // staging starts from the stored value
-                    if (whole) *(uint4 *)(theta + i0) = stored;
-                    else for (int e = 0; e < VN && i0 + e < numel; ++e) theta[i0 + e] = Prec<DT>::f2w(th[e]);   // exact
-                }
-#pragma unroll
-                for (int e = 0; e < VN; ++e) {
-                    a[e] = __builtin_fmaf(eps, z[e], th[e]);
-                    b[e] = __builtin_fmaf(-eps, z[e], th[e]);
-                }
-                if (whole) {
-                    *(uint4 *)(dp + i0) = pack16<DT>(a);
-                    *(uint4 *)(dm + i0) = pack16<DT>(b);
-                } else {
-                    for (int e = 0; e < VN && i0 + e < numel; ++e) {
-                        dp[i0 + e] = Prec<DT>::f2w(a[e]);
-                        dm[i0 + e] = Prec<DT>::f2w(b[e]);
-                    }
-                }
-            }
-        }
-        return;
-    }
-
-    // transposing tile: rows r0.., cols c0..  (cols % 4 == 0 is guaranteed by the caller)
-    // A thread owns a 4 x 4 patch (4 adjacent rows, one Philox block each), so each of its 4 columns goes
-    // into the transposed LDS tile as one packed store of 4 adjacent rows (no 2-byte scatter).
+    constexpr int G = kStageThreads / 256;
     constexpr int T = (int)kStageTile;
     constexpr int LD = T + 4;                       // row stride: keeps 8-byte (16-byte for fp32) alignment, spreads banks
-    __shared__ __attribute__((aligned(16))) W sp[T * LD];
-    __shared__ __attribute__((aligned(16))) W sm[SINGLE ? 1 : T * LD];
-    const uint32_t r0 = (tile / d.tiles_c) * T, c0 = (tile % d.tiles_c) * T;
-    const uint32_t rb = threadIdx.x / 16, cb = threadIdx.x % 16;
-    const uint32_t c = c0 + 4 * cb;
-    W vp[4][4], vm[4][4];                           // [row in patch][column in patch]
-    [[maybe_unused]] float fp[4][4], fm[4][4];      // bf16: kept in fp32 until two rows of a column are converted together
-    // Rows or columns past the edge of the matrix are computed like the others, from element 0 (always there),
-    // and never leave LDS: one straight-line body for the four rows lets the compiler share the generator's
-    // constants between them instead of setting them up again behind every bounds branch.
+    constexpr int kTileF4 = G * T * LD * (int)sizeof(W) / 16;
+    static_assert(kTileF4 >= kRayleighFirst, "the table's virtual base must not fall below the LDS allocation");
+    // LDS: the groups' tile buffers first, the radius table behind them (its unused leading entries overlap the tile
+    // area only virtually: load_rayleigh_cells and normal_pair touch entries >= kRayleighFirst alone)
+    __shared__ float4 lds[kTileF4 + (SINGLE ? 0 : kRayleighLast - kRayleighFirst)];
+    [[maybe_unused]] const float4 *const ln_tab = lds + kTileF4 - kRayleighFirst;
+    if constexpr (!SINGLE) load_rayleigh_cells(lds + kTileF4 - kRayleighFirst);
+    const int grp = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8));
+    const uint32_t tix = threadIdx.x & 255u;
+    W *const sbuf = (W *)lds + grp * T * LD;
+    float us = 0.0f;
+    if constexpr (UPD != 0) us = *dev_scale;
+    for (uint32_t blk0 = blockIdx.x * G; blk0 < batch.total_tiles; blk0 += gridDim.x * G) {
+        const uint32_t blk = blk0 + (uint32_t)grp;
+        const bool active = blk < batch.total_tiles;
+        int di = 0;
+        for (int i = 1; i < batch.n; ++i)
+            if (batch.d[i].first_tile <= blk) di = i;
+        const StageDesc &d = batch.d[di];
+        const uint32_t tile = blk - d.first_tile;
+        W *const theta = (W *)const_cast<void *>(d.src);      // written only when UPD != 0
+        const W *src = theta;
+        W *__restrict__ dp = (W *)d.dst_plus;
+        W *__restrict__ dm = (W *)d.dst_minus;
+        const uint64_t numel = (uint64_t)d.rows * d.cols;
+        const bool transposing = active && d.transpose != 0;
+
+        if (active && !d.transpose) {
+            constexpr int kIter = kStageFlatTile / (256 * VN);
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const uint32_t r = r0 + 4 * rb + it;
-        const bool valid = r < d.rows && c < d.cols;
-        const uint64_t i0 = valid ? (uint64_t)r * d.cols + c : 0;
-        W raw[4];
-        if constexpr (sizeof(W) == 2) *(uint2 *)raw = *(const uint2 *)(src + i0);
-        else *(uint4 *)raw = *(const uint4 *)(src + i0);
-        if constexpr (SINGLE) {
+            for (int it = 0; it < kIter; ++it) {
+                const uint64_t i0 = (uint64_t)tile * kStageFlatTile + (uint64_t)(it * 256 + tix) * VN;
+                if (i0 >= numel) break;
+                float z[VN];
+                if constexpr (!SINGLE) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) vp[it][e] = raw[e];
-        } else {
-            float z[4];
-            normal4(philox_block(seed, d.tid, i0 / 4), z, ln_tab);
-            if constexpr (UPD != 0) {
-                float zu[4];
-                normal4(philox_block(upd_seed, d.tid, i0 / 4), zu, ln_tab);
-                u32x4 rr{};
-                if constexpr (UPD == 2) rr = philox_block(upd_seed, d.tid, i0 / 4, 3u);
-                const uint32_t rw[4] = {rr.x, rr.y, rr.z, rr.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float v = __builtin_fmaf(us, zu[e], Prec<DT>::w2f(raw[e]));
-                    if constexpr (UPD == 2) raw[e] = DT == kBF16 ? sr_to_bf16(v, rw[e]) : sr_to_f16(v, rw[e]);
-                    else raw[e] = Prec<DT>::f2w(v);
+                    for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
                 }
-                if (valid) {
-                    if constexpr (sizeof(W) == 2) *(uint2 *)(theta + i0) = *(const uint2 *)raw;
-                    else *(uint4 *)(theta + i0) = *(const uint4 *)raw;
+                const bool whole = i0 + VN <= numel;
+                if constexpr (SINGLE) {
+                    if (whole) *(uint4 *)(dp + i0) = *(const uint4 *)(src + i0);
+                    else for (int e = 0; e < VN && i0 + e < numel; ++e) dp[i0 + e] = src[i0 + e];
+                } else {
+                    float th[VN], a[VN], b[VN];
+                    if (whole) {
+                        unpack16<DT>(*(const uint4 *)(src + i0), th);
+                    } else {
+                        for (int e = 0; e < VN; ++e) th[e] = i0 + e < numel ? Prec<DT>::w2f(src[i0 + e]) : 0.0f;
+                    }
+                    if constexpr (UPD != 0) {
+                        float zu[VN];
+#pragma unroll
+                        for (int bk = 0; bk < VN / 4; ++bk) normal4(philox_block(upd_seed, d.tid, i0 / 4 + bk), zu + 4 * bk, ln_tab);
+#pragma unroll
+                        for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(us, zu[e], th[e]);
+                        uint4 stored;
+                        if constexpr (UPD == 2) {
+                            uint32_t rw[VN];
+#pragma unroll
+                            for (int bk = 0; bk < VN / 4; ++bk) {
+                                const u32x4 r = philox_block(upd_seed, d.tid, i0 / 4 + bk, 3u);
+                                rw[4 * bk] = r.x; rw[4 * bk + 1] = r.y; rw[4 * bk + 2] = r.z; rw[4 * bk + 3] = r.w;
+                            }
+                            stored = pack16_sr<DT>(th, rw);
+                        } else {
+                            stored = pack16<DT>(th);
+                        }
+                        unpack16<DT>(stored, th);          // staging starts from the stored value
+                        if (whole) *(uint4 *)(theta + i0) = stored;
+                        else for (int e = 0; e < VN && i0 + e < numel; ++e) theta[i0 + e] = Prec<DT>::f2w(th[e]);   // exact
+                    }
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) {
+                        a[e] = __builtin_fmaf(eps, z[e], th[e]);
+                        b[e] = __builtin_fmaf(-eps, z[e], th[e]);
+                    }
+                    if (whole) {
+                        *(uint4 *)(dp + i0) = pack16<DT>(a);
+                        *(uint4 *)(dm + i0) = pack16<DT>(b);
+                    } else {
+                        for (int e = 0; e < VN && i0 + e < numel; ++e) {
+                            dp[i0 + e] = Prec<DT>::f2w(a[e]);
+                            dm[i0 + e] = Prec<DT>::f2w(b[e]);
+                        }
+                    }
                 }
             }
+        }
+
+        // transposing tile: rows r0.., cols c0..  (cols % 4 == 0 is guaranteed by the caller)
+        // A thread owns a 4 x 4 patch (4 adjacent rows, one Philox block each), so each of its 4 columns goes
+        // into the transposed LDS tile as one packed store of 4 adjacent rows (no 2-byte scatter).
+        const uint32_t tiles_c = transposing ? d.tiles_c : 1u;
+        const uint32_t r0 = (tile / tiles_c) * T, c0 = (tile % tiles_c) * T;
+        const uint32_t rb = tix / 16, cb = tix % 16;
+        const uint32_t c = c0 + 4 * cb;
+        // packed columns of the patch, per sign: col[e] = rows 0..3 of column e (2-byte types: two words; fp32: four)
+        constexpr int CW = (int)sizeof(W) == 2 ? 2 : 4;
+        uint32_t colp[4][CW], colm[SINGLE ? 1 : 4][CW];
+        if (transposing) {
+            // Rows or columns past the edge of the matrix are computed like the others, from element 0 (always there),
+            // and never leave LDS: one straight-line body for the four rows lets the compiler share the generator's
+            // constants between them instead of setting them up again behind every bounds branch.
+            float fpv[4][4];
+            [[maybe_unused]] float fmv[4][4];
+            W rawv[4][4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const uint32_t r = r0 + 4 * rb + it;
+                const bool valid = r < d.rows && c < d.cols;
+                const uint64_t i0 = valid ? (uint64_t)r * d.cols + c : 0;
+                W raw[4];
+                if constexpr (sizeof(W) == 2) *(uint2 *)raw = *(const uint2 *)(src + i0);
+                else *(uint4 *)raw = *(const uint4 *)(src + i0);
+                if constexpr (SINGLE) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) rawv[it][e] = raw[e];
+                } else {
+                    float z[4];
+                    normal4(philox_block(seed, d.tid, i0 / 4), z, ln_tab);
+                    if constexpr (UPD != 0) {
+                        float zu[4];
+                        normal4(philox_block(upd_seed, d.tid, i0 / 4), zu, ln_tab);
+                        u32x4 rr{};
+                        if constexpr (UPD == 2) rr = philox_block(upd_seed, d.tid, i0 / 4, 3u);
+                        const uint32_t rw[4] = {rr.x, rr.y, rr.z, rr.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float v = __builtin_fmaf(us, zu[e], Prec<DT>::w2f(raw[e]));
+                            if constexpr (UPD == 2) raw[e] = DT == kBF16 ? sr_to_bf16(v, rw[e]) : sr_to_f16(v, rw[e]);
+                            else raw[e] = Prec<DT>::f2w(v);
+                        }
+                        if (valid) {
+                            if constexpr (sizeof(W) == 2) *(uint2 *)(theta + i0) = *(const uint2 *)raw;
+                            else *(uint4 *)(theta + i0) = *(const uint4 *)raw;
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float th = Prec<DT>::w2f(raw[e]);
+                        fpv[it][e] = __builtin_fmaf(eps, z[e], th);
+                        fmv[it][e] = __builtin_fmaf(-eps, z[e], th);
+                    }
+                }
+            }
+            // round into the storage type, four rows of a column side by side
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float th = Prec<DT>::w2f(raw[e]);
-                if constexpr (DT == kBF16) {
-                    fp[it][e] = __builtin_fmaf(eps, z[e], th);
-                    fm[it][e] = __builtin_fmaf(-eps, z[e], th);
+                if constexpr (SINGLE) {
+                    if constexpr (sizeof(W) == 2) {
+                        colp[e][0] = (uint32_t)rawv[0][e] | ((uint32_t)rawv[1][e] << 16);
+                        colp[e][1] = (uint32_t)rawv[2][e] | ((uint32_t)rawv[3][e] << 16);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) colp[e][r] = __float_as_uint(rawv[r][e]);
+                    }
+                } else if constexpr (DT == kBF16) {
+                    // one conversion instruction rounds two rows of the column (nearest even, as the scalar conversion does)
+                    typedef float f32x2 __attribute__((ext_vector_type(2)));
+                    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                    auto pk = [](float lo, float hi) { return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2)); };
+                    colp[e][0] = pk(fpv[0][e], fpv[1][e]); colp[e][1] = pk(fpv[2][e], fpv[3][e]);
+                    colm[e][0] = pk(fmv[0][e], fmv[1][e]); colm[e][1] = pk(fmv[2][e], fmv[3][e]);
+                } else if constexpr (DT == kFP16) {
+                    colp[e][0] = (uint32_t)Prec<DT>::f2w(fpv[0][e]) | ((uint32_t)Prec<DT>::f2w(fpv[1][e]) << 16);
+                    colp[e][1] = (uint32_t)Prec<DT>::f2w(fpv[2][e]) | ((uint32_t)Prec<DT>::f2w(fpv[3][e]) << 16);
+                    colm[e][0] = (uint32_t)Prec<DT>::f2w(fmv[0][e]) | ((uint32_t)Prec<DT>::f2w(fmv[1][e]) << 16);
+                    colm[e][1] = (uint32_t)Prec<DT>::f2w(fmv[2][e]) | ((uint32_t)Prec<DT>::f2w(fmv[3][e]) << 16);
                 } else {
-                    vp[it][e] = Prec<DT>::f2w(__builtin_fmaf(eps, z[e], th));
-                    vm[it][e] = Prec<DT>::f2w(__builtin_fmaf(-eps, z[e], th));
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) { colp[e][r] = __float_as_uint(fpv[r][e]); colm[e][r] = __float_as_uint(fmv[r][e]); }
                 }
             }
         }
-    }
+        // one sign at a time through the group's tile: columns in, barrier, rows of the transposed result out
+        auto tile_in = [&](const uint32_t (&col)[4][CW]) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        W *dstp = sp + (4 * cb + e) * LD + 4 * rb, *dstm = sm + (4 * cb + e) * LD + 4 * rb;
-        if constexpr (DT == kBF16 && !SINGLE) {
-            // one conversion instruction rounds two rows of the column (nearest even, as the scalar conversion does)
-            typedef float f32x2 __attribute__((ext_vector_type(2)));
-            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-            auto pk = [](float lo, float hi) { return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2)); };
-            *(uint2 *)dstp = uint2{pk(fp[0][e], fp[1][e]), pk(fp[2][e], fp[3][e])};
-            *(uint2 *)dstm = uint2{pk(fm[0][e], fm[1][e]), pk(fm[2][e], fm[3][e])};
-            continue;
-        }
-        W colp[4] = {vp[0][e], vp[1][e], vp[2][e], vp[3][e]};
-        W colm[4] = {vm[0][e], vm[1][e], vm[2][e], vm[3][e]};
-        if constexpr (sizeof(W) == 2) {
-            *(uint2 *)dstp = *(const uint2 *)colp;
-            if constexpr (!SINGLE) *(uint2 *)dstm = *(const uint2 *)colm;
-        } else {
-            *(uint4 *)dstp = *(const uint4 *)colp;
-            if constexpr (!SINGLE) *(uint4 *)dstm = *(const uint4 *)colm;
-        }
-    }
-    __syncthreads();
-    // write: output row = source column c0 + tid/4, 16 consecutive source rows starting at r0 + 16*(tid%4)
-    const uint32_t oc = threadIdx.x / 4, seg = 16 * (threadIdx.x % 4);
-    if (c0 + oc < d.cols) {
-        const uint64_t o0 = (uint64_t)(c0 + oc) * d.rows + r0 + seg;
-        const bool full = (r0 + seg + 16 <= d.rows) && ((d.rows * sizeof(W)) % 16 == 0);
-        if (full) {
-            constexpr int NV = 16 * (int)sizeof(W) / 16;      // 16-byte pieces per 16 elements
-            using LdsVec = typename std::conditional<sizeof(W) == 2, uint2, uint4>::type;
-            constexpr int PER = 16 / (int)sizeof(LdsVec);     // LDS reads per 16-byte piece
+            for (int e = 0; e < 4; ++e) {
+                W *dst = sbuf + (4 * cb + e) * LD + 4 * rb;
+                if constexpr (sizeof(W) == 2) *(uint2 *)dst = uint2{col[e][0], col[e][1]};
+                else *(uint4 *)dst = uint4{col[e][0], col[e][1], col[e][2], col[e][3]};
+            }
+        };
+        auto tile_out = [&](W *__restrict__ out) {
+            // output row = source column c0 + tix/4, 16 consecutive source rows starting at r0 + 16*(tix%4)
+            const uint32_t oc = tix / 4, seg = 16 * (tix % 4);
+            if (c0 + oc >= d.cols) return;
+            const uint64_t o0 = (uint64_t)(c0 + oc) * d.rows + r0 + seg;
+            const bool full = (r0 + seg + 16 <= d.rows) && ((d.rows * sizeof(W)) % 16 == 0);
+            if (full) {
+                constexpr int NV = 16 * (int)sizeof(W) / 16;      // 16-byte pieces per 16 elements
+                using LdsVec = typename std::conditional<sizeof(W) == 2, uint2, uint4>::type;
+                constexpr int PER = 16 / (int)sizeof(LdsVec);     // LDS reads per 16-byte piece
 #pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                LdsVec pp[PER], pm[PER];
+                for (int v = 0; v < NV; ++v) {
+                    LdsVec pp[PER];
 #pragma unroll
-                for (int j = 0; j < PER; ++j) {
-                    pp[j] = ((const LdsVec *)(sp + oc * LD + seg))[v * PER + j];
-                    if constexpr (!SINGLE) pm[j] = ((const LdsVec *)(sm + oc * LD + seg))[v * PER + j];
+                    for (int j = 0; j < PER; ++j) pp[j] = ((const LdsVec *)(sbuf + oc * LD + seg))[v * PER + j];
+                    ((uint4 *)(out + o0))[v] = *(const uint4 *)pp;
                 }
-                ((uint4 *)(dp + o0))[v] = *(const uint4 *)pp;
-                if constexpr (!SINGLE) ((uint4 *)(dm + o0))[v] = *(const uint4 *)pm;
+            } else {
+                for (uint32_t e = 0; e < 16 && r0 + seg + e < d.rows; ++e) out[o0 + e] = sbuf[oc * LD + seg + e];
             }
-        } else {
-            for (uint32_t e = 0; e < 16 && r0 + seg + e < d.rows; ++e) {
-                dp[o0 + e] = sp[oc * LD + seg + e];
-                if constexpr (!SINGLE) dm[o0 + e] = sm[oc * LD + seg + e];
-            }
+        };
+        if (transposing) tile_in(colp);
+        __syncthreads();
+        if (transposing) tile_out(dp);
+        if constexpr (!SINGLE) {
+            __syncthreads();
+            if (transposing) tile_in(colm);
+            __syncthreads();
+            if (transposing) tile_out(dm);
         }
+        __syncthreads();        // the tile is read out before the next round writes it
     }
 }
 
@@ -468,6 +561,23 @@ hipError_t launch_normal_pairs(const uint32_t *words, float *z, uint64_t n_pairs
     return hipGetLastError();
 }
 
+// Persistent launches: `per_cu` workgroups per CU (what the kernel's LDS and wave slots allow), never more than
+// there are chunks.
+static hipError_t persistent_grid(uint64_t work, int per_cu, unsigned *grid)
+{
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, v = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        n_cu = v > 0 ? v : 1;
+    }
+    const uint64_t cap = (uint64_t)n_cu * per_cu;
+    *grid = (unsigned)(work < cap ? work : cap);
+    return hipSuccess;
+}
+
 template <int DT>
 static hipError_t axpy_launch_t(const TensorDesc *descs, int n_desc, const TensorDesc &single, uint64_t chunk_offset,
                                 uint64_t chunks, uint64_t seed, float scale, const float *dev_scale, bool stochastic,
@@ -475,15 +585,17 @@ static hipError_t axpy_launch_t(const TensorDesc *descs, int n_desc, const Tenso
 {
     if (chunks == 0) return hipSuccess;
     if (chunks > 0x7fffffffull) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)chunks), block(256);
+    unsigned g = 0;
+    if (hipError_t e = persistent_grid(chunks, ZO_AXPY_PER_CU, &g); e != hipSuccess) return e;
+    const dim3 grid(g), block(kStreamThreads);
     if constexpr (DT != kFP32) {
         if (stochastic) {
-            axpy_z_kernel<DT, true><<<grid, block, 0, s>>>(descs, n_desc, single, chunk_offset, seed, scale, dev_scale);
+            axpy_z_kernel<DT, true><<<grid, block, 0, s>>>(descs, n_desc, single, chunk_offset, (uint32_t)chunks, seed, scale, dev_scale);
             return hipGetLastError();
         }
     }
     if (stochastic) return hipErrorInvalidValue;          // fp32 storage has nothing to round stochastically
-    axpy_z_kernel<DT, false><<<grid, block, 0, s>>>(descs, n_desc, single, chunk_offset, seed, scale, dev_scale);
+    axpy_z_kernel<DT, false><<<grid, block, 0, s>>>(descs, n_desc, single, chunk_offset, (uint32_t)chunks, seed, scale, dev_scale);
     return hipGetLastError();
 }
 
@@ -505,15 +617,17 @@ static hipError_t axpy_multi_launch_t(const TensorDesc *descs, int n_desc, uint6
 {
     if (chunks == 0 || upd.n == 0) return hipSuccess;
     if (chunks > 0x7fffffffull || upd.n < 0 || upd.n > kMaxUpdates || !descs || !dev_scales) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)chunks), block(256);
+    unsigned g = 0;
+    if (hipError_t e = persistent_grid(chunks, 4, &g); e != hipSuccess) return e;
+    const dim3 grid(g), block(kStreamThreads);
     if constexpr (DT != kFP32) {
         if (stochastic) {
-            axpy_z_multi_kernel<DT, true><<<grid, block, 0, s>>>(descs, n_desc, chunk_offset, upd, dev_scales);
+            axpy_z_multi_kernel<DT, true><<<grid, block, 0, s>>>(descs, n_desc, chunk_offset, (uint32_t)chunks, upd, dev_scales);
             return hipGetLastError();
         }
     }
     if (stochastic) return hipErrorInvalidValue;
-    axpy_z_multi_kernel<DT, false><<<grid, block, 0, s>>>(descs, n_desc, chunk_offset, upd, dev_scales);
+    axpy_z_multi_kernel<DT, false><<<grid, block, 0, s>>>(descs, n_desc, chunk_offset, (uint32_t)chunks, upd, dev_scales);
     return hipGetLastError();
 }
 
@@ -564,7 +678,11 @@ hipError_t launch_stage(const StageBatch &b, int dtype, uint64_t seed, float eps
     if (b.total_tiles == 0) return hipSuccess;
     if (upd_mode < 0 || upd_mode > 2 || (upd_mode != 0 && (single_copy || !dev_scale)) || (upd_mode == 2 && dtype == kFP32))
         return hipErrorInvalidValue;
-    const dim3 grid(b.total_tiles), block(256);
+    // LDS per workgroup of four groups: 58 KiB (16-bit types), 92 KiB (fp32), 34 / 68 KiB for the plain copy
+    constexpr int G = kStageThreads / 256;
+    unsigned g = 0;
+    if (hipError_t e = persistent_grid((b.total_tiles + G - 1) / G, dtype == kFP32 ? 1 : ZO_STAGE_PER_CU, &g); e != hipSuccess) return e;
+    const dim3 grid(g), block(kStageThreads);
 #define ZO_STAGE(DT)                                                                                              \
     if (single_copy) stage_kernel<DT, true, 0><<<grid, block, 0, s>>>(b, seed, eps, 0, nullptr);                   \
     else if (upd_mode == 0) stage_kernel<DT, false, 0><<<grid, block, 0, s>>>(b, seed, eps, 0, nullptr);           \

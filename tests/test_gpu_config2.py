@@ -27,15 +27,24 @@ def test_config2_ten_steps_against_the_oracle():
     for (lp, lm, g), st in zip(got, gold["steps"]):
         assert abs(lp / st["l_plus"] - 1) < 2e-2 and abs(lm / st["l_minus"] - 1) < 2e-2, (st, lp, lm)
         noise = max(noise, abs(lp - st["l_plus"]), abs(lm - st["l_minus"]))
-    # sign of g wherever the oracle's loss difference stands clear of the measured bf16 loss noise; the rest are listed
+    # The configuration asks for 2e-2 on the losses; what bf16 activations really cost at this size is two orders
+    # below that (measured 1e-4 .. 2e-4 absolute on losses of 10.97), and the sign test below depends on it: bound it.
+    assert noise < 2.9e-4, noise
+    # sign of g wherever the oracle's loss difference stands clear of the bf16 loss noise; the rest are listed.  The
+    # oracle's |l+ - l-| is at least 1.19e-3 > 4 x 2.9e-4 on eight of the ten seeds of this golden file (3.7e-4 and
+    # 4.1e-4 on the other two), so at least eight are checked whenever the noise bound holds.
     checked, below = 0, []
     for (lp, lm, g), st in zip(got, gold["steps"]):
-        if abs(st["l_plus"] - st["l_minus"]) > 4 * noise:
+        diff = st["l_plus"] - st["l_minus"]
+        if abs(diff) > 4 * noise:
             assert np.sign(g) == np.sign(st["g"]), (st, g)
+            # and its size: the two losses' errors are at most `noise` each
+            assert abs(g - st["g"]) <= 2 * noise / (2 * c["eps"]) + 1e-9, (st, g)
             checked += 1
         else:
             below.append(st["seed"])
     print("bf16 loss noise %.3g; sign(g) checked on %d of 10 steps; below 4x noise: seeds %s" % (noise, checked, below))
     print("gpu g:", ["%.3f" % r[2] for r in got], "oracle g:", ["%.3f" % st["g"] for st in gold["steps"]])
+    assert checked >= 8, (checked, below, noise)
     assert zo_amd.zo_device_flags(mdl.handle) == 0
     mdl.close()

@@ -83,12 +83,13 @@ def test_linear_pm(dtype, m_half, n, k, epi):
     got = y.double().cpu().numpy()
     scale = np.sqrt(k) * 0.05 + 1.0           # size of a dot product of k such terms (+ bias / residual)
     if dtype == zi.FP32:
-        tol = 1e-12 * scale
+        bound = 4e-12 * scale
     elif epi in (0, 1):
-        tol = (1.0 * ULP[dtype] + 1e-5) * scale       # one output rounding + fp32 accumulation
+        # one rounding of the output, half a unit in its own last place, + fp32 accumulation over k terms in tile order
+        bound = ULP[dtype] * np.abs(want) + 2e-5 * scale
     else:
-        tol = 2e-5 * scale                            # fp32 accumulation order only
-    assert np.max(np.abs(got - want)) < tol * 4
+        bound = 4e-5 * scale                          # fp32 accumulation order only
+    assert np.max(np.abs(got - want) / bound) < 1.0
 
 
 @pytest.mark.parametrize("dtype", [zi.FP32, zi.BF16, zi.FP16])
@@ -109,8 +110,12 @@ def test_attention(dtype, n_seq, seq, heads, dh):
 
 
 @pytest.mark.parametrize("dtype", [zi.FP32, zi.BF16, zi.FP16])
-@pytest.mark.parametrize("m_half,d,vocab", [(6, 64, 512), (70, 128, 1000), (20, 64, 50272)])
+@pytest.mark.parametrize("m_half,d,vocab", [(6, 64, 512), (70, 128, 1000), (20, 64, 50272),
+                                            (2100, 192, 4104), (1024, 768, 50272)])
 def test_lmhead_ce(dtype, m_half, d, vocab):
+    """The last two shapes take the persistent 256-wide kernel in the 2-byte types (at least 128 tiles, d >= 192): its
+    per-row (max, sum-exp) slots, target-logit store, ragged vocabulary tail (4104 = 16 x 256 + 8, 50272 = 196 x 256 + 96)
+    and ragged row tail (2100 = 8 x 256 + 52)."""
     rng = np.random.Generator(np.random.PCG64(vocab + d))
     x = rng.standard_normal((2 * m_half, d))
     xd = act_to_dev(x, dtype)
@@ -118,6 +123,7 @@ def test_lmhead_ce(dtype, m_half, d, vocab):
     e = [_weights(rng, (vocab, d), dtype, 0.1) for _ in range(2)]
     target = rng.integers(0, vocab, size=2 * m_half).astype(np.int32)
     target[::5] = -1
+    target[1], target[2], target[m_half + 1] = vocab - 1, vocab - vocab % 256 if vocab % 256 else vocab - 256, (vocab - 1) // 256 * 256 - 1
     row_loss = torch.full((2 * m_half,), 7.0, dtype=torch.float64, device=DEV)
     scratch = torch.empty(zo_amd.zo_kernel_lmhead_scratch_bytes(dtype, m_half, vocab), dtype=torch.uint8, device=DEV)
     zo_amd.zo_kernel_lmhead_ce(xd, to_dev(e[0], dtype), to_dev(e[1], dtype), torch.from_numpy(target).to(DEV), row_loss, scratch,
@@ -129,8 +135,8 @@ def test_lmhead_ce(dtype, m_half, d, vocab):
         lse = np.log(np.exp(logits - mx[:, None]).sum(-1)) + mx
         tg = target[s * m_half:(s + 1) * m_half]
         want = np.where(tg >= 0, lse - logits[np.arange(m_half), np.maximum(tg, 0)], 0.0)
-        tol = 1e-11 if dtype == zi.FP32 else 2e-5      # logits stay in fp32: accumulation order only
-        assert np.max(np.abs(got[s * m_half:(s + 1) * m_half] - want)) < tol * 10
+        tol = 1e-10 if dtype == zi.FP32 else 2e-4      # logits stay in fp32 (values up to ~10): accumulation order only
+        assert np.max(np.abs(got[s * m_half:(s + 1) * m_half] - want)) < tol
 
 
 def _tiny_model(**kw):

@@ -74,7 +74,7 @@ def _theta_sample(rng, n, dtype):
 
 
 @pytest.mark.parametrize("dtype", [zi.FP32, zi.BF16, zi.FP16])
-@pytest.mark.parametrize("n", [1, 7, 8, 4096, 4097, 3 * 4096 + 13, 1 << 20])
+@pytest.mark.parametrize("n", [1, 7, 8, 4096, 4097, 8192, 8193, 3 * 8192 + 13, 1 << 20])
 def test_axpy_bits_exact(dtype, n):
     rng = np.random.Generator(np.random.PCG64(n))
     theta = _theta_sample(rng, max(n, 8), dtype)[:n]
