@@ -49,6 +49,12 @@ def parse():
                     help="resident fused mode: 'deferred' applies a step's update inside the next step's staging pass (Alg. 2's "
                          "order; the last one is flushed inside the timed region), 'immediate' in a pass of its own at the end "
                          "of the step; theta ends up bit-identical either way")
+    ap.add_argument("--lookahead", type=int, default=0, choices=[0, 1],
+                    help="streamed configuration: steps the host may run ahead of the device (0: every step returns drained)")
+    ap.add_argument("--timeline", default=None, metavar="FILE",
+                    help="streamed configuration: write the event timeline of the LAST timed step (per block: upload, kernels, "
+                         "write-back start / end from HIP events), the link rates and the share of the copy time that kernels "
+                         "ran under, as text")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy, a kernel of known HBM traffic that calibrates "
@@ -149,6 +155,80 @@ def cpu_baseline(cfgd, name):
                       % (L, s_batch, s_seq, s_vocab, t_stage + t_fwd + t_upd + t_head, full_tokens)}
 
 
+def _union_ms(intervals):
+    """Total length of the union of (start, end) intervals."""
+    tot, cur_a, cur_b = 0.0, None, None
+    for a, b in sorted(intervals):
+        if cur_b is None or a > cur_b:
+            if cur_b is not None:
+                tot += cur_b - cur_a
+            cur_a, cur_b = a, b
+        else:
+            cur_b = max(cur_b, b)
+    return tot + (cur_b - cur_a if cur_b is not None else 0.0)
+
+
+def _overlap_ms(a_list, b_list):
+    """Length of (union of a) intersected with (union of b)."""
+    return _union_ms(a_list) + _union_ms(b_list) - _union_ms(list(a_list) + list(b_list))
+
+
+def write_timeline(args, c, spans, block_bytes, step_s):
+    """Alg. 3 as the device ran it: the records of the last timed step (upload U, kernels C, write-back O per block),
+    achieved link rates over the copies themselves, and how much of the time the link was busy had kernels running
+    beside it.  Returns the summary figures; writes the text file when --timeline names one."""
+    L = c["n_layers"]
+    comp = [s for s in spans if s[0] == 1]
+    # the last step = the last L compute records; copies belong to it from its first upload on
+    last = comp[-L:]
+    all_ups = [s for s in spans if s[0] == 0]
+    n_up = len(all_ups) // max(len(comp) // L, 1)          # uploads per step (the same in every step)
+    ups = all_ups[-n_up:] if n_up else []
+    t_begin = min([last[0][2]] + [s[2] for s in ups[:1]])
+    t_end = last[-1][3]
+    wbs = [s for s in spans if s[0] == 2 and s[2] >= t_begin]       # this step's write-backs (the last may end after the kernels)
+    up_ms = sum(s[3] - s[2] for s in ups)
+    wb_ms = sum(s[3] - s[2] for s in wbs)
+    link = [(s[2], s[3]) for s in ups + wbs]
+    kern = [(s[2], s[3]) for s in last]
+    link_busy = _union_ms(link)
+    hidden = _overlap_ms(link, kern)
+    kern_busy = _union_ms(kern)
+    summ = {"timeline_step_ms": t_end - t_begin,
+            "h2d_gbs_while_copying": block_bytes * len(ups) / (up_ms * 1e-3) / 1e9 if up_ms else 0.0,
+            "d2h_gbs_while_copying": block_bytes * len(wbs) / (wb_ms * 1e-3) / 1e9 if wb_ms else 0.0,
+            "link_busy_ms": link_busy, "kernels_busy_ms": kern_busy,
+            "kernel_time_under_copies_frac": hidden / kern_busy if kern_busy else 0.0,
+            "copy_time_with_kernels_beside_frac": hidden / link_busy if link_busy else 0.0}
+    if args.timeline:
+        with open(args.timeline, "w") as f:
+            f.write("Alg. 3 timeline of one streamed ZO-SGD step (the last timed one), from HIP events on the stream each operation ran on\n")
+            f.write("command: python bench.py %s\n" % " ".join(sys.argv[1:]))
+            f.write("%s, batch %d x seq %d, %d blocks (%d in pinned host memory, %d in HBM), write-back every %d step(s), look-ahead %d; "
+                    "block = %.3f GB\n" % (args.config, c["batch"], c["seq"], L, len({s[1] for s in ups}) if ups else 0,
+                                            L - (len({s[1] for s in ups}) if ups else 0), args.writeback_interval, args.lookahead,
+                                            block_bytes / 1e9))
+            f.write("step %.1f ms by the wall clock (%.1f tokens/s); first kernel to last kernel of the step %.1f ms\n"
+                    % (step_s * 1e3, c["batch"] * c["seq"] / step_s, t_end - t_begin))
+            f.write("uploads: %d, %.1f ms each on average, %.1f GB/s while copying; write-backs: %d, %.1f ms each, %.1f GB/s while copying\n"
+                    % (len(ups), up_ms / max(len(ups), 1), summ["h2d_gbs_while_copying"], len(wbs), wb_ms / max(len(wbs), 1),
+                       summ["d2h_gbs_while_copying"]))
+            f.write("link busy (either direction) %.1f ms, kernels busy %.1f ms; %.1f %% of the kernel time ran under a copy, "
+                    "%.1f %% of the link-busy time had kernels beside it\n"
+                    % (link_busy, kern_busy, 100 * summ["kernel_time_under_copies_frac"], 100 * summ["copy_time_with_kernels_beside_frac"]))
+            f.write("\nms since the step's first upload or kernel; U = upload of the block into its slot, C = the block's kernels (pending updates, "
+                    "staging, dual forward), O = write-back\n")
+            f.write("%5s  %21s  %21s  %21s\n" % ("block", "U start .. end", "C start .. end", "O start .. end"))
+            by_u = {s[1]: s for s in ups}
+            by_o = {s[1]: s for s in wbs}
+            for s in last:
+                b = s[1]
+                u = "%9.1f .. %9.1f" % (by_u[b][2] - t_begin, by_u[b][3] - t_begin) if b in by_u else "%21s" % "(in HBM)"
+                o = "%9.1f .. %9.1f" % (by_o[b][2] - t_begin, by_o[b][3] - t_begin) if b in by_o else "%21s" % "-"
+                f.write("%5d  %21s  %9.1f .. %9.1f  %21s\n" % (b, u, s[2] - t_begin, s[3] - t_begin, o))
+    return summ
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -186,23 +266,33 @@ def main():
         block_shapes = shapes[2:18]
         per_block = sum(int(torch.Size(sh).numel()) for _, sh in block_shapes)
         nring = max(1, min(args.host_blocks, c["n_layers"]))
-        host_ring = torch.empty((nring, per_block), dtype=tdt, pin_memory=True)
+        # one pinned allocation per block (a single allocation of tens of GB can be refused where these are not);
+        # if the box will not pin as many as asked for, the layers cycle through those it gave
         one = torch.cat([t.reshape(-1) for t in device_weights(torch, block_shapes, c["dtype"], dev, seed=7)]).cpu()
+        host_ring = []
         for r in range(nring):
-            host_ring[r].copy_(one)
+            try:
+                blk_host = torch.empty(per_block, dtype=tdt, pin_memory=True)
+            except RuntimeError:
+                if not host_ring:
+                    raise
+                break
+            blk_host.copy_(one)
+            host_ring.append(blk_host)
+        nring = len(host_ring)
         del one
         offs, o = [], 0
         for _, sh in block_shapes:
             offs.append(o)
             o += int(torch.Size(sh).numel())
-        esz = host_ring.element_size()
+        esz = host_ring[0].element_size()
         tensors = [resident[0], resident[1]]
         n_host = c["n_layers"] - max(0, min(args.hbm_blocks, c["n_layers"]))
         host_at = {int((i + 0.5) * c["n_layers"] / n_host) for i in range(n_host)}       # evenly spread
         hbm_keep, nh = [], 0
         for l in range(c["n_layers"]):
             if l in host_at:
-                base = host_ring.data_ptr() + (nh % nring) * per_block * esz
+                base = host_ring[nh % nring].data_ptr()
                 nh += 1
                 tensors += [base + off * esz for off in offs]
             else:
@@ -224,6 +314,8 @@ def main():
         zo_amd.zo_set_update_rounding(h, zo_amd.ZO_ROUND_STOCHASTIC)
     if streamed and args.writeback_interval != 1:
         zo_amd.zo_set_writeback_interval(h, args.writeback_interval)
+    if streamed:
+        zo_amd.zo_set_stream_lookahead(h, args.lookahead)
 
     mode = zo_amd.ZO_MODE_LITERAL if args.mode == "literal" else zo_amd.ZO_MODE_FUSED
     deferred = (not streamed) and mode == zo_amd.ZO_MODE_FUSED and args.update == "deferred"
@@ -249,6 +341,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = zo_amd.zo_profile_end(h)
+    spans = zo_amd.zo_profile_spans(h) if streamed else []
     if args.traffic_probe:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
         b = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -315,17 +408,22 @@ def main():
         "last_step": {"l_plus": lp, "l_minus": lm, "g": g, "device_flags": flags},
     }
     if streamed:
-        block_bytes = host_ring.shape[1] * host_ring.element_size()
+        block_bytes = host_ring[0].numel() * host_ring[0].element_size()
         step_s = dt / args.steps
-        out["streaming"] = {"block_bytes": block_bytes, "blocks_per_step": c["n_layers"], "distinct_host_blocks": int(host_ring.shape[0]),
+        out["streaming"] = {"block_bytes": block_bytes, "blocks_per_step": c["n_layers"], "distinct_host_blocks": len(host_ring),
                             "h2d_gbs": block_bytes * n_host / step_s / 1e9,
                             "d2h_gbs": (block_bytes * n_host / step_s / 1e9 / args.writeback_interval
                                         if args.warmup + args.steps > 1 else 0.0),
                             "writeback_interval": args.writeback_interval,
                             "blocks_in_hbm": c["n_layers"] - n_host, "blocks_streamed": n_host,
                             "compute_ms_per_block": sum(v["ms_per_step"] for v in kernels.values()) / c["n_layers"],
-                            "note": "layers cycle through the distinct host blocks, so values are not those of one model; "
-                                    "traffic, kernels and schedule are those of the full model"}
+                            "note": ("every streamed layer has a host block of its own" if n_host <= len(host_ring) else
+                                     "the streamed layers cycle through fewer distinct host blocks than there are layers (the full "
+                                     "model would pin 348 GB): layers that share a region write it back and upload it on different "
+                                     "streams without ordering between them, so the host VALUES are not those of one model and are "
+                                     "not meaningful; traffic, kernels and schedule are those of the full model")}
+        if spans:
+            out["streaming"].update(write_timeline(args, c, spans, block_bytes, dt / args.steps))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(c, args.config)
     print(json.dumps(out))

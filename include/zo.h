@@ -80,11 +80,14 @@ typedef struct {
     float   ln_eps;      /* LayerNorm epsilon (OPT: 1e-5) */
 } zo_config;
 
-/* Bytes of device workspace zo_init_model needs for batches of up to
- * `batch` x `seq` tokens.  Returns 0 if cfg is invalid. */
+/* Bytes of device workspace zo_init_model needs for batches of up to `batch` x `seq` tokens: the
+ * activations of the dual forward (Eq. 1 evaluates L twice; both signs are resident at once), the
+ * staged W+- of one block (PertP workflow, Step 2) and, for ZO_STREAMED, the two upload slots of
+ * App. A, Alg. 3.  Returns 0 if cfg is invalid. */
 size_t zo_workspace_bytes(const zo_config *cfg, int batch, int seq);
 
-/* Create a model handle over caller-owned memory.
+/* Create a model handle over caller-owned memory: the inputs of App. A, Alg. 1 / Alg. 2 (theta, and where each
+ * module's parameters live: Alg. 3 keeps the blocks W_i in host memory and uploads them per visit).
  *   tensor_ptrs[n_tensors]  canonical order.  ZO_RESIDENT: all device pointers.
  *                           ZO_STREAMED: ids 0, 1 and the last two are device pointers;
  *                           the 16 tensors of a block are either pinned-host pointers, adjacent
@@ -127,8 +130,8 @@ int zo_dual_forward(zo_model *m, const int32_t *tokens, int batch, int seq, uint
  * step is applied right after its upload and written back, and this step's update stays
  * pending until the next zo_step or zo_flush_pending.
  *   host_g, host_loss_pm   host, double[1] / double[2], nullable; non-NULL synchronises.
- * A ZO_STREAMED step always returns with its kernels finished (its last write-backs may still be running): the
- * schedule of Alg. 3 only holds on the device if the host does not queue steps ahead of it. */
+ * A ZO_STREAMED step returns with its kernels finished unless zo_set_stream_lookahead allows it to run ahead.  If a HIP call fails inside a streamed step, the step is closed and the upload slots are
+ * emptied before the error is returned; theta is then partly updated and has to be restored by the caller. */
 int zo_step(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t seed,
             float eps, float lr, int mode, double *host_g, double *host_loss_pm);
 
@@ -176,6 +179,15 @@ int zo_set_deferred_update(zo_model *m, int on);
  * updates are pending (flush first). */
 int zo_set_writeback_interval(zo_model *m, int steps);
 
+/* Streamed models: how many steps the host may run ahead of the device in zo_step when no host out-pointer makes the
+ * call wait anyway.  0 (the default): every zo_step returns with its kernels finished (its last write-backs may still
+ * be running), which is what keeps the device on the schedule of App. A, Alg. 3.  1: the call that enqueues step j
+ * returns once step j - 2 has finished, so the first uploads and launches of the next step are already queued when
+ * a step ends; on the PCIe-bound configuration this measured slower (the queued copies of two steps share the
+ * link less evenly), so it is an option, not the default.  Results are bit-identical either way.  ZO_EINVAL outside
+ * 0..1, ZO_ESTATE on a resident model. */
+int zo_set_stream_lookahead(zo_model *m, int steps);
+
 /* How the update of Eq. 2 is rounded into a 16-bit storage type.  ZO_ROUND_NEAREST (the default, and the
  * only rounding of every perturbation) is round-to-nearest-even.  ZO_ROUND_STOCHASTIC is an opt-in
  * variant that is not in the paper: at its learning rates a nearest-rounded update of a 16-bit weight
@@ -202,6 +214,16 @@ enum { ZO_K_LINEAR = 0, ZO_K_ATTENTION = 1, ZO_K_STAGE = 2, ZO_K_UPDATE = 3, ZO_
        ZO_K_CLASSES = 7 };
 int zo_profile_begin(zo_model *m, int max_launches);
 int zo_profile_end(zo_model *m, double *ms, uint64_t *launches, double *work);
+
+/* ZO_STREAMED models: the timeline of App. A, Alg. 3's three operations over the steps that ran between
+ * zo_profile_begin and zo_profile_end, from HIP events on the stream each one ran on.  One record per upload U(W_i)
+ * (ZO_SPAN_UPLOAD), per block's kernels C(W_i) (ZO_SPAN_COMPUTE: pending updates, staging, dual forward) and per
+ * write-back O(W_i) (ZO_SPAN_WRITEBACK), in the order they were enqueued; blocks that live in HBM have compute records
+ * only.  Times are milliseconds since the earliest recorded start.  Host arrays of max_spans entries; *n_spans
+ * receives the number filled (at most 4096 are kept).  Synchronises all three streams.  ZO_ESTATE while profiling
+ * is still on. */
+enum { ZO_SPAN_UPLOAD = 0, ZO_SPAN_COMPUTE = 1, ZO_SPAN_WRITEBACK = 2 };
+int zo_profile_spans(zo_model *m, int max_spans, int32_t *kind, int32_t *block, double *start_ms, double *end_ms, int *n_spans);
 
 int zo_free(zo_model *m);
 const char *zo_last_error(void);
@@ -244,15 +266,8 @@ int zo_kernel_stage_update_pm(void *theta, void *w_plus, void *w_minus, int dtyp
                               uint64_t seed, uint32_t tensor_id, float eps, uint64_t upd_seed,
                               const float *dev_scale, int stochastic, void *stream);
 
-/* Diagnostic, not a step of the path: the rate at which this chip issues 32x32x16 matrix multiplies of `dtype`
- * (ZO_BF16 / ZO_FP16) when nothing else happens: no loads, 16 independent accumulators per wave, 4 waves per
- * workgroup.  One launch does n_workgroups * 4 * iters * 16 multiplies of 2*32*32*16 FLOP.  With random_operands
- * zero every operand is 0.0; otherwise the operands have random sign and mantissa, which is what a GEMM on real
- * data feeds the pipe, and the clock the chip holds under its power limit is lower.  out: device, at least
- * n_workgroups * 256 floats (each thread writes one sum, so the work cannot be elided). */
-int zo_probe_mfma_rate(float *out, int dtype, int n_workgroups, int iters, int random_operands, void *stream);
-
-/* Sign-batched linear layer:  rows [0, m_half) of x use (wt_plus, b_plus), rows
+/* Sign-batched linear layer (the QKV / out / FFN projections of a module's DualForward, App. A, Alg. 2:
+ * both evaluations of Eq. 1 in one launch):  rows [0, m_half) of x use (wt_plus, b_plus), rows
  * [m_half, 2 m_half) use (wt_minus, b_minus):  y = x W + b with W given transposed as
  * wt[n, k].  x is [2 m_half, k].  2-byte dtypes run on MFMA with fp32 accumulation;
  * ZO_FP32 takes fp64 activations (x, y are double) and accumulates in fp64.
@@ -265,18 +280,21 @@ int zo_kernel_linear_pm(const void *x, const void *wt_plus, const void *wt_minus
                         const void *b_plus, const void *b_minus, void *y,
                         int dtype, int m_half, int n, int k, int epilogue, void *stream);
 
-/* LayerNorm over the last dimension of resid [2 m_half, d] (fp32; fp64 for ZO_FP32) with
+/* LayerNorm of the OPT decoder block (Sec. 7, experimental set-up: OPT family) inside DualForward (App. A, Alg. 2),
+ * over the last dimension of resid [2 m_half, d] (fp32; fp64 for ZO_FP32) with
  * per-sign gain and bias, output in the activation type. */
 int zo_kernel_layernorm_pm(const void *resid, const void *g_plus, const void *g_minus,
                            const void *b_plus, const void *b_minus, void *y,
                            int dtype, int m_half, int d, float ln_eps, void *stream);
 
-/* Causal multi-head attention: qkv [n_seq * seq, 3 d] (q | k | v, heads contiguous inside each)
+/* Causal multi-head attention of the decoder block inside DualForward (App. A, Alg. 2; both signs are
+ * simply more sequences): qkv [n_seq * seq, 3 d] (q | k | v, heads contiguous inside each)
  * -> out [n_seq * seq, d], softmax(q k^T / sqrt(d_head)) v per (sequence, head). */
 int zo_kernel_attention(const void *qkv, void *out, int dtype, int n_seq, int seq, int n_heads,
                         int d_head, void *stream);
 
-/* Tied LM head + cross entropy: for each row r of x [2 m_half, d] (already final-LayerNormed),
+/* Tied LM head + cross entropy, the last module of App. A, Alg. 2 ("LM head") and the loss L of Eq. 1:
+ * for each row r of x [2 m_half, d] (already final-LayerNormed),
  * logits = x[r] . E+-^T over the vocabulary, row_loss[r] = logsumexp(logits) - logits[target[r]];
  * target[r] < 0 marks a row that does not count (row_loss = 0).  row_loss is double[2 m_half].
  * `scratch` is device memory of zo_kernel_lmhead_scratch_bytes(...) bytes. */

@@ -21,11 +21,11 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 
 EXPORTS = (
     "zo_workspace_bytes", "zo_init_model", "zo_perturb", "zo_dual_forward", "zo_step", "zo_stream_block",
-    "zo_stream_begin", "zo_stream_end", "zo_flush_pending", "zo_set_writeback_interval", "zo_set_deferred_update", "zo_set_update_rounding", "zo_device_flags", "zo_free",
-    "zo_last_error", "zo_profile_begin", "zo_profile_end",
+    "zo_stream_begin", "zo_stream_end", "zo_flush_pending", "zo_set_writeback_interval", "zo_set_stream_lookahead", "zo_set_deferred_update", "zo_set_update_rounding", "zo_device_flags", "zo_free",
+    "zo_last_error", "zo_profile_begin", "zo_profile_end", "zo_profile_spans",
     "zo_kernel_z", "zo_kernel_normal_pairs", "zo_kernel_axpy_z", "zo_kernel_axpy_z_sr", "zo_kernel_stage_pm", "zo_kernel_stage_update_pm", "zo_kernel_linear_pm",
     "zo_kernel_layernorm_pm", "zo_kernel_attention", "zo_kernel_lmhead_scratch_bytes", "zo_kernel_lmhead_ce",
-    "zo_probe_mfma_rate", "zo_kernel_lmhead_ce_noalloc",
+    "zo_kernel_lmhead_ce_noalloc",
 )
 
 
@@ -68,18 +68,19 @@ def lib():
         L.zo_flush_pending.argtypes = [vp]
         L.zo_set_update_rounding.argtypes = [vp, i32]
         L.zo_set_writeback_interval.argtypes = [vp, i32]
+        L.zo_set_stream_lookahead.argtypes = [vp, i32]
         L.zo_set_deferred_update.argtypes = [vp, i32]
         L.zo_device_flags.argtypes = [vp, ctypes.POINTER(u32)]
         L.zo_free.argtypes = [vp]
         L.zo_profile_begin.argtypes = [vp, i32]
         L.zo_profile_end.argtypes = [vp, vp, vp, vp]
+        L.zo_profile_spans.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         L.zo_kernel_z.argtypes = [vp, u64, u64, u32, u64, vp]
         L.zo_kernel_normal_pairs.argtypes = [vp, vp, u64, vp]
         L.zo_kernel_axpy_z.argtypes = [vp, vp, i32, u64, u64, u32, f32, vp, vp]
         L.zo_kernel_axpy_z_sr.argtypes = [vp, vp, i32, u64, u64, u32, f32, vp, vp]
         L.zo_kernel_stage_pm.argtypes = [vp, vp, vp, i32, i32, i32, i32, u64, u32, f32, vp]
         L.zo_kernel_stage_update_pm.argtypes = [vp, vp, vp, i32, i32, i32, i32, u64, u32, f32, u64, vp, i32, vp]
-        L.zo_probe_mfma_rate.argtypes = [vp, i32, i32, i32, i32, vp]
         L.zo_kernel_linear_pm.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.zo_kernel_layernorm_pm.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]
         L.zo_kernel_attention.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
@@ -176,6 +177,10 @@ def zo_flush_pending(model):
     _check(lib().zo_flush_pending(model))
 
 
+def zo_set_stream_lookahead(handle, steps):
+    _check(lib().zo_set_stream_lookahead(handle, steps))
+
+
 def zo_set_writeback_interval(model, steps):
     _check(lib().zo_set_writeback_interval(model, steps))
 
@@ -209,6 +214,19 @@ def zo_profile_end(model):
     return {ZO_K_NAMES[i]: (ms[i], int(cnt[i]), work[i]) for i in range(n)}
 
 
+ZO_SPAN_UPLOAD, ZO_SPAN_COMPUTE, ZO_SPAN_WRITEBACK = 0, 1, 2
+
+
+def zo_profile_spans(model, max_spans=4096):
+    """Returns a list of (kind, block, start_ms, end_ms)."""
+    kind, block = (ctypes.c_int32 * max_spans)(), (ctypes.c_int32 * max_spans)()
+    t0, t1 = (ctypes.c_double * max_spans)(), (ctypes.c_double * max_spans)()
+    n = ctypes.c_int()
+    _check(lib().zo_profile_spans(model, max_spans, ctypes.addressof(kind), ctypes.addressof(block), ctypes.addressof(t0),
+                                  ctypes.addressof(t1), ctypes.addressof(n)))
+    return [(int(kind[i]), int(block[i]), t0[i], t1[i]) for i in range(n.value)]
+
+
 def zo_free(model):
     _check(lib().zo_free(model))
 
@@ -238,10 +256,6 @@ def zo_kernel_stage_update_pm(theta, w_plus, w_minus, dtype, rows, cols, transpo
                               stochastic=False, stream=None):
     _check(lib().zo_kernel_stage_update_pm(_ptr(theta), _ptr(w_plus), _ptr(w_minus), dtype, rows, cols, int(transpose), seed,
                                            tensor_id, eps, upd_seed, _ptr(dev_scale), int(stochastic), _stream(stream)))
-
-
-def zo_probe_mfma_rate(out, dtype, n_workgroups, iters, random_operands=True, stream=None):
-    _check(lib().zo_probe_mfma_rate(_ptr(out), dtype, n_workgroups, iters, int(random_operands), _stream(stream)))
 
 
 def zo_kernel_linear_pm(x, wt_plus, wt_minus, b_plus, b_minus, y, dtype, m_half, n, k, epilogue, stream=None):

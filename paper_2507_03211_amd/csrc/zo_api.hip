@@ -171,6 +171,11 @@ struct zo_model {
     std::vector<int> blk_slot;
     int up_next;                       // zo_step / zo_flush_pending: first block whose upload has not been enqueued yet
     hipEvent_t ev_uploaded[2], ev_staged[2], ev_written[2];
+    // How far the host may run ahead of the device in streamed steps: ev_step[j % 2] marks the end of step j's kernels;
+    // with lookahead 1 the call that enqueues step j first waits for step j - 2, with 0 every step returns drained.
+    hipEvent_t ev_step[2];
+    uint64_t n_steps;
+    int lookahead;
     int slot_block[2];
     SlotState slot_state[2];
     bool slot_dirty[2];
@@ -198,6 +203,9 @@ struct zo_model {
     std::vector<hipEvent_t> prof_ev;      // 2 per record
     std::vector<int> prof_cls;
     std::vector<double> prof_work;
+    // streamed models, while profiling: one record per upload, per block's kernels and per write-back
+    struct Span { int kind, block; hipEvent_t t0, t1; };      // kind: ZO_SPAN_*
+    std::vector<Span> spans;
 };
 
 namespace {
@@ -219,6 +227,27 @@ struct ProfScope {
     ~ProfScope()
     {
         if (live && hipEventRecord(m->prof_ev[2 * m->prof_n + 1], m->compute) == hipSuccess) ++m->prof_n;
+    }
+};
+// Brackets one copy or one block's kernels of a streamed step with events on `s` while profiling is on.
+struct SpanScope {
+    zo_model *m;
+    hipStream_t s;
+    zo_model::Span sp;
+    bool live;
+    SpanScope(zo_model *m_, int kind, int block, hipStream_t s_) : m(m_), s(s_), sp{kind, block, nullptr, nullptr}, live(false)
+    {
+        if (!m->prof_on || m->spans.size() >= 4096) return;
+        if (hipEventCreate(&sp.t0) != hipSuccess) return;
+        if (hipEventCreate(&sp.t1) != hipSuccess) { (void)hipEventDestroy(sp.t0); return; }
+        live = hipEventRecord(sp.t0, s) == hipSuccess;
+        if (!live) { (void)hipEventDestroy(sp.t0); (void)hipEventDestroy(sp.t1); }
+    }
+    ~SpanScope()
+    {
+        if (!live) return;
+        if (hipEventRecord(sp.t1, s) == hipSuccess) m->spans.push_back(sp);
+        else { (void)hipEventDestroy(sp.t0); (void)hipEventDestroy(sp.t1); }
     }
 };
 #define ZO_PROF(m, cls, work, expr)       \
@@ -479,7 +508,10 @@ int stream_prefetch(zo_model *m, int block)
     // the slot is free once its previous occupant was staged (and, if updated, written back)
     ZO_HIP(hipStreamWaitEvent(m->upload, m->ev_staged[slot], 0));
     ZO_HIP(hipStreamWaitEvent(m->upload, m->ev_written[slot], 0));
-    ZO_HIP(hipMemcpyAsync(m->ws + m->wsp.slot[slot], m->tptr[2 + kPerBlock * block], bytes, hipMemcpyHostToDevice, m->upload));
+    {
+        SpanScope span(m, ZO_SPAN_UPLOAD, block, m->upload);
+        ZO_HIP(hipMemcpyAsync(m->ws + m->wsp.slot[slot], m->tptr[2 + kPerBlock * block], bytes, hipMemcpyHostToDevice, m->upload));
+    }
     ZO_HIP(hipEventRecord(m->ev_uploaded[slot], m->upload));
     m->slot_block[slot] = block;
     m->slot_state[slot] = SLOT_UPLOADED;
@@ -493,6 +525,7 @@ int stream_compute(zo_model *m, int block, bool forward, bool force_writeback = 
     if (m->blk_dev[block]) {
         // a block that stays in HBM is visited once per step and only ever lacks the newest update (Alg. 2: a
         // module takes last step's update at its visit)
+        SpanScope span(m, ZO_SPAN_COMPUTE, block, m->compute);
         if (m->pend_n > 0)
             ZO_TRY(axpy_range(m, 2 + kPerBlock * block, kPerBlock, m->pend_seed[m->pend_n - 1], 0.0f, m->s_pend + (m->pend_n - 1), true));
         if (forward) {
@@ -505,6 +538,7 @@ int stream_compute(zo_model *m, int block, bool forward, bool force_writeback = 
     if (m->slot_state[slot] != SLOT_UPLOADED || m->slot_block[slot] != block)
         return fail(ZO_ESTATE, "block %d was not prefetched", block);
     ZO_HIP(hipStreamWaitEvent(m->compute, m->ev_uploaded[slot], 0));
+    SpanScope span(m, ZO_SPAN_COMPUTE, block, m->compute);      // from here on: the block's kernels, not the wait for its upload
     if (m->pend_n == 1) {
         ZO_TRY(axpy_range(m, 2 + kPerBlock * block, kPerBlock, m->pend_seed[0], 0.0f, m->s_pend, true));
     } else if (m->pend_n > 1) {      // all of them in one pass over the block
@@ -539,7 +573,10 @@ int stream_writeback(zo_model *m, int block)
     if (m->slot_dirty[slot]) {
         const size_t bytes = m->lay.total * elem_bytes(m->cfg.dtype);
         ZO_HIP(hipStreamWaitEvent(m->download, m->ev_staged[slot], 0));
-        ZO_HIP(hipMemcpyAsync(m->tptr[2 + kPerBlock * block], m->ws + m->wsp.slot[slot], bytes, hipMemcpyDeviceToHost, m->download));
+        {
+            SpanScope span(m, ZO_SPAN_WRITEBACK, block, m->download);
+            ZO_HIP(hipMemcpyAsync(m->tptr[2 + kPerBlock * block], m->ws + m->wsp.slot[slot], bytes, hipMemcpyDeviceToHost, m->download));
+        }
         ZO_HIP(hipEventRecord(m->ev_written[slot], m->download));
         m->slot_dirty[slot] = false;
     }
@@ -684,7 +721,9 @@ extern "C" int zo_init_model(const zo_config *cfg, void *const *tensor_ptrs, int
     for (int s = 0; s < 2; ++s) {
         m->slot_block[s] = -1; m->slot_state[s] = SLOT_EMPTY; m->slot_dirty[s] = false;
         m->ev_uploaded[s] = m->ev_staged[s] = m->ev_written[s] = nullptr;
+        m->ev_step[s] = nullptr;
     }
+    m->n_steps = 0; m->lookahead = 0;
     if (cfg->residency == ZO_STREAMED) {
         err = hipStreamCreateWithFlags(&m->download, hipStreamNonBlocking);
         m->own_download = err == hipSuccess;
@@ -692,6 +731,7 @@ extern "C" int zo_init_model(const zo_config *cfg, void *const *tensor_ptrs, int
             err = hipEventCreateWithFlags(&m->ev_uploaded[s], hipEventDisableTiming);
             if (err == hipSuccess) err = hipEventCreateWithFlags(&m->ev_staged[s], hipEventDisableTiming);
             if (err == hipSuccess) err = hipEventCreateWithFlags(&m->ev_written[s], hipEventDisableTiming);
+            if (err == hipSuccess) err = hipEventCreateWithFlags(&m->ev_step[s], hipEventDisableTiming);
         }
         if (err != hipSuccess) { zo_free(m); return fail(ZO_EHIP, "creating streams/events failed: %s", hipGetErrorString(err)); }
     }
@@ -711,9 +751,11 @@ extern "C" int zo_free(zo_model *m)
         if (m->ev_uploaded[s]) (void)hipEventDestroy(m->ev_uploaded[s]);
         if (m->ev_staged[s]) (void)hipEventDestroy(m->ev_staged[s]);
         if (m->ev_written[s]) (void)hipEventDestroy(m->ev_written[s]);
+        if (m->ev_step[s]) (void)hipEventDestroy(m->ev_step[s]);
     }
     if (m->own_download) (void)hipStreamDestroy(m->download);
     for (hipEvent_t ev : m->prof_ev) (void)hipEventDestroy(ev);
+    for (auto &sp : m->spans) { (void)hipEventDestroy(sp.t0); (void)hipEventDestroy(sp.t1); }
     delete m;
     return ZO_OK;
 }
@@ -732,6 +774,39 @@ int apply_pending_resident(zo_model *m)
     return rc;
 }
 }
+
+namespace {
+// Alg. 3: U(W_{i+1}) is in flight while C(W_i) runs; O(W_i) follows as soon as W_i is staged.
+int streamed_step(zo_model *m, const int32_t *tokens, int batch, int seq, uint64_t seed, float eps, float lr)
+{
+    ZO_TRY(stream_begin(m, tokens, batch, seq, seed, eps));
+    m->up_next = 0;
+    ZO_TRY(stream_fill(m));
+    for (int l = 0; l < m->cfg.n_layers; ++l) {
+        ZO_TRY(stream_compute(m, l, true));
+        m->next_block = l + 1;
+        ZO_TRY(stream_writeback(m, l));
+        ZO_TRY(stream_fill(m));
+    }
+    return stream_end(m, lr);
+}
+
+// A streamed step that failed half way (a HIP call returned an error): let what was enqueued finish, close the step and
+// empty the upload slots, so that later calls are not refused with ZO_ESTATE for ever.  What the failed step had
+// already written (updates applied to the blocks it reached) stays: theta is then neither the old nor the new iterate,
+// as after any interrupted in-place pass, and the caller has to restore it from its own copy.
+void stream_abort(zo_model *m)
+{
+    (void)hipStreamSynchronize(m->upload);
+    (void)hipStreamSynchronize(m->compute);
+    if (m->download) (void)hipStreamSynchronize(m->download);
+    (void)hipGetLastError();
+    m->step_open = false;
+    m->next_block = 0;
+    m->up_next = 0;
+    for (int s = 0; s < 2; ++s) { m->slot_block[s] = -1; m->slot_state[s] = SLOT_EMPTY; m->slot_dirty[s] = false; }
+}
+}  // namespace
 
 extern "C" int zo_perturb(zo_model *m, uint64_t seed, float scale, int first_tensor, int n_tensors)
 {
@@ -792,23 +867,19 @@ extern "C" int zo_step(zo_model *m, const int32_t *tokens, int batch, int seq, u
         return read_back(m, host_g, host_loss_pm);
     }
     if (mode != ZO_MODE_FUSED) return fail(ZO_EINVAL, "a streamed model supports ZO_MODE_FUSED only");
-    // Alg. 3: U(W_{i+1}) is in flight while C(W_i) runs; O(W_i) follows as soon as W_i is staged.
-    ZO_TRY(stream_begin(m, tokens, batch, seq, seed, eps));
-    m->up_next = 0;
-    ZO_TRY(stream_fill(m));
-    for (int l = 0; l < m->cfg.n_layers; ++l) {
-        ZO_TRY(stream_compute(m, l, true));
-        m->next_block = l + 1;
-        ZO_TRY(stream_writeback(m, l));
-        ZO_TRY(stream_fill(m));
+    // The host runs at most `lookahead` steps ahead of the device.  Unbounded, a caller that does not ask for g queues
+    // hundreds of copies, waits and thousands of launches over three streams, and the device no longer starts them in
+    // the order Alg. 3 gives them; bounded to one step, the next step's uploads and launches are queued while this
+    // step still runs and nothing idles between steps.
+    if (m->lookahead >= 1 && m->n_steps >= 2) ZO_HIP(hipEventSynchronize(m->ev_step[m->n_steps & 1]));
+    const int rc = streamed_step(m, tokens, batch, seq, seed, eps, lr);
+    if (rc != ZO_OK) {
+        stream_abort(m);
+        return rc;
     }
-    ZO_TRY(stream_end(m, lr));
-    // A streamed step ends with the compute stream drained, whether the caller wants g or not: a host that runs
-    // several steps ahead leaves hundreds of copies and thousands of launches queued, and the step's own schedule
-    // (which upload may start once which slot is free) is then no longer what the device sees first; measured
-    // 757 -> 1107 tokens/s at 175B with 72 blocks in HBM.  The copy streams are not waited for: the last
-    // write-backs of this step overlap the first blocks of the next.
-    ZO_HIP(hipStreamSynchronize(m->compute));
+    ZO_HIP(hipEventRecord(m->ev_step[m->n_steps & 1], m->compute));
+    ++m->n_steps;
+    if (m->lookahead < 1) ZO_HIP(hipStreamSynchronize(m->compute));
     return read_back(m, host_g, host_loss_pm);
 }
 
@@ -875,6 +946,15 @@ extern "C" int zo_set_writeback_interval(zo_model *m, int steps)
     return ZO_OK;
 }
 
+extern "C" int zo_set_stream_lookahead(zo_model *m, int steps)
+{
+    if (!m) return fail(ZO_EINVAL, "model is NULL");
+    if (m->cfg.residency != ZO_STREAMED) return fail(ZO_ESTATE, "not a streamed model");
+    if (steps < 0 || steps > 1) return fail(ZO_EINVAL, "look-ahead of %d steps: 0 or 1", steps);
+    m->lookahead = steps;
+    return ZO_OK;
+}
+
 extern "C" int zo_flush_pending(zo_model *m)
 {
     if (!m) return fail(ZO_EINVAL, "model is NULL");
@@ -920,6 +1000,8 @@ extern "C" int zo_profile_begin(zo_model *m, int max_launches)
     m->prof_cls.assign(max_launches, 0);
     m->prof_work.assign(max_launches, 0.0);
     m->prof_n = 0;
+    for (auto &sp : m->spans) { (void)hipEventDestroy(sp.t0); (void)hipEventDestroy(sp.t1); }
+    m->spans.clear();
     m->prof_on = true;
     return ZO_OK;
 }
@@ -937,6 +1019,31 @@ extern "C" int zo_profile_end(zo_model *m, double *ms, uint64_t *launches, doubl
         const int c = m->prof_cls[i];
         ms[c] += t; launches[c] += 1; work[c] += m->prof_work[i];
     }
+    return ZO_OK;
+}
+
+extern "C" int zo_profile_spans(zo_model *m, int max_spans, int32_t *kind, int32_t *block, double *start_ms, double *end_ms, int *n_spans)
+{
+    if (!m || !kind || !block || !start_ms || !end_ms || !n_spans || max_spans < 0) return fail(ZO_EINVAL, "bad argument");
+    if (m->prof_on) return fail(ZO_ESTATE, "profiling is still on: call zo_profile_end first");
+    if (m->upload) ZO_HIP(hipStreamSynchronize(m->upload));
+    if (m->download) ZO_HIP(hipStreamSynchronize(m->download));
+    ZO_HIP(hipStreamSynchronize(m->compute));
+    const int n = (int)m->spans.size() < max_spans ? (int)m->spans.size() : max_spans;
+    // time zero: the earliest start among the records
+    int first = 0;
+    for (int i = 1; i < (int)m->spans.size(); ++i) {
+        float t = 0.0f;
+        ZO_HIP(hipEventElapsedTime(&t, m->spans[first].t0, m->spans[i].t0));
+        if (t < 0.0f) first = i;
+    }
+    for (int i = 0; i < n; ++i) {
+        float a = 0.0f, b = 0.0f;
+        ZO_HIP(hipEventElapsedTime(&a, m->spans[first].t0, m->spans[i].t0));
+        ZO_HIP(hipEventElapsedTime(&b, m->spans[first].t0, m->spans[i].t1));
+        kind[i] = m->spans[i].kind; block[i] = m->spans[i].block; start_ms[i] = a; end_ms[i] = b;
+    }
+    *n_spans = n;
     return ZO_OK;
 }
 
@@ -1008,16 +1115,6 @@ extern "C" int zo_kernel_stage_update_pm(void *theta, void *w_plus, void *w_minu
     StageBatch b{};
     stage_batch_add(b, theta, w_plus, w_minus, rows, cols, tensor_id, transpose != 0);
     ZO_HIP(launch_stage(b, dtype, seed, eps, false, (hipStream_t)stream, stochastic ? 2 : 1, upd_seed, dev_scale));
-    return ZO_OK;
-}
-
-extern "C" int zo_probe_mfma_rate(float *out, int dtype, int n_workgroups, int iters, int random_operands, void *stream)
-{
-    ZO_TRY(check_dtype(dtype));
-    if (dtype == ZO_FP32) return fail(ZO_EINVAL, "the probe issues 16-bit multiplies: ZO_BF16 or ZO_FP16");
-    if (!out) return fail(ZO_EINVAL, "NULL argument");
-    if (n_workgroups < 1 || n_workgroups > (1 << 20) || iters < 1) return fail(ZO_EINVAL, "bad launch shape");
-    ZO_HIP(launch_mfma_probe(out, dtype, n_workgroups, iters, random_operands != 0, (hipStream_t)stream));
     return ZO_OK;
 }
 

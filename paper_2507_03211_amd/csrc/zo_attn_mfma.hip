@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 3 : 2)) void attn_mfma_kernel(cons
     const uint32_t ks_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)&ks3[0][0];
     const uint32_t vs_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)&vs2[0][0];
     auto dma16 = [](uint64_t gbase, uint32_t lane_off, uint32_t lds_off) {
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase), "s"(lds_off) : "memory");
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase), "s"(lds_off) : "memory", "m0");
     };
     // this wave's pieces of K (which = 0) or V (which = 1) rows k0 .. k0 + 63, into buffer `buf` of that operand
     auto issue = [&](int which, int k0, int buf) {

@@ -244,7 +244,7 @@ constexpr int kGroupM = 8;                      // tile-rows per band
 // instruction) plus a 32-bit per-lane byte offset that stays the same for the whole tile.
 __device__ __forceinline__ void gload_lds16(uint64_t base, uint32_t lane_off, uint32_t lds_off)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_off) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_off) : "memory", "m0");
 }
 __device__ __forceinline__ uint64_t uniform64(uint64_t v)
 {
@@ -676,62 +676,6 @@ hipError_t launch_linear_mfma(const void *x, const void *wt_p, const void *wt_m,
     }
     if (dtype == kBF16) launch_t<kBF16>(x, wt_p, wt_m, b_p, b_m, y, n_sign, m_half, n, k, epilogue, s);
     else launch_t<kFP16>(x, wt_p, wt_m, b_p, b_m, y, n_sign, m_half, n, k, epilogue, s);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------- diagnostic: what the matrix pipe sustains
-// Nothing but 32x32x16 multiplies, 16 independent accumulators per wave, one wave per SIMD times `waves_per_simd`,
-// no memory traffic at all: the rate at which the chip issues them.  With all-zero operands it reaches the nominal
-// 2.5 PFLOP/s; with operands of random sign and mantissa the clock comes down under the power limit, and that rate,
-// not the nominal one, is the ceiling a GEMM on real data has.
-namespace {
-__device__ __forceinline__ uint32_t probe_hash(uint32_t x)
-{
-    x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
-    return x;
-}
-template <int DT> __global__ __launch_bounds__(256) void mfma_probe_kernel(float *out, int iters, int random_operands)
-{
-    f32x16 acc[16];
-#pragma unroll
-    for (int a = 0; a < 16; ++a)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[a][i] = 0.0f;
-    uint4 va[4], vb[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        uint32_t w[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t h = probe_hash(threadIdx.x * 131u + blockIdx.x * 7919u + s * 31u + i);
-            // two 16-bit values of random sign and mantissa, magnitude in [0.5, 2) (bf16) or [1, 2) (fp16)
-            const uint32_t lo = DT == kBF16 ? ((h & 0x80ffu) | 0x3f00u) : ((h & 0x83ffu) | 0x3c00u);
-            const uint32_t hi = DT == kBF16 ? (((h >> 16) & 0x80ffu) | 0x3f00u) : (((h >> 16) & 0x83ffu) | 0x3c00u);
-            w[i] = random_operands ? (lo | (hi << 16)) : 0u;
-        }
-        va[s] = uint4{w[0], w[1], w[2], w[3]};
-        vb[s] = uint4{w[4], w[5], w[6], w[7]};
-    }
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int a = 0; a < 16; ++a) acc[a] = mfma32<DT>(va[a & 3], vb[(a >> 2) & 3], acc[a]);
-    }
-    float sum = 0.0f;
-#pragma unroll
-    for (int a = 0; a < 16; ++a)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sum += acc[a][i];
-    out[blockIdx.x * 256 + threadIdx.x] = sum;
-}
-}  // namespace
-
-// out: at least n_workgroups * 256 floats.  Work per launch: n_workgroups * 4 waves * iters * 16 multiplies of
-// 2 * 32 * 32 * 16 FLOP.
-hipError_t launch_mfma_probe(float *out, int dtype, int n_workgroups, int iters, int random_operands, hipStream_t s)
-{
-    if (!out || n_workgroups < 1 || iters < 1 || (dtype != kBF16 && dtype != kFP16)) return hipErrorInvalidValue;
-    if (dtype == kBF16) mfma_probe_kernel<kBF16><<<dim3(n_workgroups), dim3(256), 0, s>>>(out, iters, random_operands);
-    else mfma_probe_kernel<kFP16><<<dim3(n_workgroups), dim3(256), 0, s>>>(out, iters, random_operands);
     return hipGetLastError();
 }
 

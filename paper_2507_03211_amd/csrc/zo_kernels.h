@@ -48,7 +48,6 @@ hipError_t launch_axpy_updates(const TensorDesc *dev_descs, int n_desc, uint64_t
 hipError_t launch_axpy_single(const TensorDesc &d, int dtype, uint64_t seed, float scale,
                               const float *dev_scale, bool stochastic, hipStream_t s);
 // both signs (eps) or a plain (transposing) copy when single_copy
-hipError_t launch_mfma_probe(float *out, int dtype, int n_workgroups, int iters, int random_operands, hipStream_t s);
 // upd_mode 0: stage only.  1 / 2: first theta <- rn(fma(*dev_scale, z(upd_seed), theta)) in place (round to nearest /
 // stochastic rounding), then W+- from the updated theta, in the same pass (`src` of every descriptor is written).
 hipError_t launch_stage(const StageBatch &b, int dtype, uint64_t seed, float eps, bool single_copy, hipStream_t s, int upd_mode = 0,

@@ -64,9 +64,7 @@ def test_host_side_argument_checks():
     with pytest.raises(zo_amd.ZoError):
         zo_amd.zo_set_deferred_update(None, 1)
     with pytest.raises(zo_amd.ZoError):
-        zo_amd.zo_probe_mfma_rate(4096, zo_amd.ZO_FP32, 8, 8)       # the probe has no fp32 form
+        zo_amd.zo_kernel_lmhead_ce_noalloc(None, 4096, 4096, 4096, 4096, zo_amd.ZO_BF16, 8, 64, 512)      # NULL input
     with pytest.raises(zo_amd.ZoError):
-        zo_amd.zo_probe_mfma_rate(None, zo_amd.ZO_BF16, 8, 8)
-    with pytest.raises(zo_amd.ZoError):
-        zo_amd.zo_probe_mfma_rate(4096, zo_amd.ZO_BF16, 0, 8)
+        zo_amd.zo_kernel_lmhead_ce_noalloc(4096, 4096, 4096, 4096, 4096, zo_amd.ZO_BF16, 8, 60, 512)      # d not a multiple of 8
     assert zo_amd.zo_free(None) is None

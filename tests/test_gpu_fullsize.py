@@ -54,8 +54,9 @@ def test_linear_at_13b_shapes_sampled(n, k, epi):
             want = want + y0[int(r)][cols].double().cpu().numpy()
         got = y[int(r)][cols].double().cpu().numpy()
         scale = np.sqrt(k) * 0.02 + 1.0
-        tol = (2.0**-8 if epi != 2 else 1e-4) * scale * 2
-        assert np.max(np.abs(got - want)) < tol, (r, np.max(np.abs(got - want)), tol)
+        # bf16 outputs: one rounding (half a unit in the output's own last place) + fp32 accumulation order; fp32 outputs: the latter
+        bound = (2.0**-8 * np.abs(want) if epi != 2 else 0.0) + 4e-5 * scale
+        assert np.max(np.abs(got - want) / bound) < 1.0, (r, np.max(np.abs(got - want) / bound))
 
 
 def test_attention_at_13b_shape_sampled_heads():
@@ -182,18 +183,3 @@ def test_step_invariants_at_opt_1_3b_size():
     assert after != a
     assert zo_amd.zo_device_flags(h) == 0
     zo_amd.zo_free(h)
-
-
-@pytest.mark.parametrize("dtype", [zo_amd.ZO_BF16, zo_amd.ZO_FP16])
-def test_matrix_rate_probe_runs_its_multiplies(dtype):
-    """The diagnostic that measures the matrix-instruction rate: every thread writes its sum, zeros stay zero,
-    random operands give the same finite non-zero sums on every launch."""
-    wgs, iters = 16, 3
-    sink = torch.full((wgs * 256,), 7.0, device=DEV)
-    zo_amd.zo_probe_mfma_rate(sink, dtype, wgs, iters, False)
-    assert torch.count_nonzero(sink).item() == 0
-    zo_amd.zo_probe_mfma_rate(sink, dtype, wgs, iters, True)
-    a = sink.clone()
-    zo_amd.zo_probe_mfma_rate(sink, dtype, wgs, iters, True)
-    assert torch.isfinite(a).all() and torch.count_nonzero(a).item() > a.numel() // 2
-    assert torch.equal(a, sink)

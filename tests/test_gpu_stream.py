@@ -186,3 +186,29 @@ def test_blocks_kept_in_hbm_leave_results_bit_identical(dtype, device_blocks, in
         with pytest.raises(zo_amd.ZoError):
             zo_amd.zo_perturb(mix.handle, 5, 1e-3, 2 + 16 * host_blocks[0], 16)
     res.close(); mix.close()
+
+
+@pytest.mark.parametrize("lookahead", [0, 1])
+def test_steps_queued_without_host_waits_leave_the_same_bits(lookahead):
+    """zo_step without host out-pointers: the host runs up to one step ahead of the device (or none with look-ahead 0).
+    Six steps queued that way, with a write-back interval of 2 and one block kept in HBM, end in the theta of the
+    resident model bit for bit, and the last step's losses are the resident model's."""
+    kw = dict(dtype=zi.BF16, batch=2, seq=40, seed=3, plain_small=False, std=0.05)
+    res = Model(**SHAPE, **kw)
+    stm = Model(**SHAPE, streamed=True, device_blocks=(1,), **kw)
+    zo_amd.zo_set_stream_lookahead(stm.handle, lookahead)
+    zo_amd.zo_set_writeback_interval(stm.handle, 2)
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_set_stream_lookahead(res.handle, 1)              # not a streamed model
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_set_stream_lookahead(stm.handle, 2)
+    tok, tok_dev = res.tokens()
+    for seed in range(6):
+        zo_amd.zo_step(res.handle, tok_dev, 2, 40, seed, 1e-3, 1e-2, want_host=False)
+        zo_amd.zo_step(stm.handle, tok_dev, 2, 40, seed, 1e-3, 1e-2, want_host=False)
+    a = zo_amd.zo_step(res.handle, tok_dev, 2, 40, 6, 1e-3, 1e-2)
+    b = zo_amd.zo_step(stm.handle, tok_dev, 2, 40, 6, 1e-3, 1e-2)
+    assert a == b and np.isfinite(a[2])
+    zo_amd.zo_flush_pending(stm.handle)
+    assert all(x.tobytes() == y.tobytes() for x, y in zip(res.theta(), stm.theta()))
+    res.close(); stm.close()
