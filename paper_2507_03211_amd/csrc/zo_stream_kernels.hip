@@ -97,6 +97,20 @@ template <int DT> __device__ __forceinline__ uint4 pack16(const float *f)
     }
 }
 
+// Descriptor i of a table in device memory, fetched through the scalar cache: the index is the same for every lane
+// of the workgroup (it depends on blockIdx and the loop count alone), which the compiler cannot see by itself; a
+// vector load here would put a memory round trip per lane in front of every chunk's address.
+typedef const __attribute__((address_space(4))) TensorDesc *DescTable;
+__device__ __forceinline__ DescTable desc_table(const TensorDesc *p) { return (DescTable)(uintptr_t)p; }
+__device__ __forceinline__ TensorDesc desc_at(DescTable t, int i)
+{
+    const int u = __builtin_amdgcn_readfirstlane(i);
+    TensorDesc d;
+    d.src = t[u].src; d.dst = t[u].dst; d.numel = t[u].numel; d.first_chunk = t[u].first_chunk; d.tid = t[u].tid; d.pad = 0;
+    return d;
+}
+__device__ __forceinline__ uint64_t desc_first_chunk(DescTable t, int i) { return t[__builtin_amdgcn_readfirstlane(i)].first_chunk; }
+
 // One chunk = kAxpyChunk consecutive elements of one tensor; workgroup w of a launch takes chunks w, w + gridDim.x, ...
 // of the launch's `total_chunks`.  SR: stochastic instead of nearest rounding into the storage type, with the random
 // word of element i taken from word i % 4 of the Philox block (i / 4, tensor, tag 3) under the same seed.
@@ -126,14 +140,14 @@ __global__ __launch_bounds__(kStreamThreads) void axpy_z_kernel(const TensorDesc
         int lo = 0, hi = n_desc - 1;
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
-            if (descs[mid].first_chunk <= chunk) lo = mid; else hi = mid - 1;
+            if (desc_first_chunk(desc_table(descs), mid) <= chunk) lo = mid; else hi = mid - 1;
         }
         di = lo;
     }
     auto desc_of = [&](uint64_t chunk) {
         if (!descs) return single;
-        while (di + 1 < n_desc && descs[di + 1].first_chunk <= chunk) ++di;
-        return descs[di];
+        while (di + 1 < n_desc && desc_first_chunk(desc_table(descs), di + 1) <= chunk) ++di;
+        return desc_at(desc_table(descs), di);
     };
     // A chunk that lies wholly inside its tensor (all but a tensor's last) is loaded one iteration ahead, into
     // registers, so that a wave never waits for memory with nothing to compute; the others take the guarded path.
@@ -244,14 +258,14 @@ __global__ __launch_bounds__(kStreamThreads) void axpy_z_multi_kernel(const Tens
         int lo = 0, hi = n_desc - 1;                      // last descriptor whose first_chunk <= chunk
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
-            if (descs[mid].first_chunk <= chunk) lo = mid; else hi = mid - 1;
+            if (desc_first_chunk(desc_table(descs), mid) <= chunk) lo = mid; else hi = mid - 1;
         }
         di = lo;
     }
     for (uint32_t c = blockIdx.x; c < total_chunks; c += gridDim.x) {
         const uint64_t chunk = (uint64_t)c + chunk_offset;
-        while (di + 1 < n_desc && descs[di + 1].first_chunk <= chunk) ++di;
-        const TensorDesc d = descs[di];
+        while (di + 1 < n_desc && desc_first_chunk(desc_table(descs), di + 1) <= chunk) ++di;
+        const TensorDesc d = desc_at(desc_table(descs), di);
         const uint64_t base = (chunk - d.first_chunk) * kAxpyChunk;
         const W *__restrict__ src = (const W *)d.src;
         W *__restrict__ dst = (W *)d.dst;
