@@ -333,7 +333,7 @@ constexpr int kStageThreads = ZO_STAGE_THREADS;       // groups of 256 threads, 
 // two 1024-thread workgroups, all 32 wave slots, share a CU next to the 24 KiB table.  The barriers of a round are
 // the same for every group whatever its tile is (flat, transposing or none).
 template <int DT, bool SINGLE, int UPD>
-__global__ __launch_bounds__(kStageThreads) void stage_kernel(StageBatch batch, uint64_t seed, float eps, uint64_t upd_seed,
+__global__ __launch_bounds__(kStageThreads) __attribute__((amdgpu_waves_per_eu((DT != kFP32 && UPD != 2) ? 8 : 4))) void stage_kernel(StageBatch batch, uint64_t seed, float eps, uint64_t upd_seed,
                                                               const float *__restrict__ dev_scale)
 {
     using W = typename Prec<DT>::W;
