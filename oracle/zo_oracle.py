@@ -181,12 +181,14 @@ class Config:
         return 4 + TENSORS_PER_BLOCK * self.n_layers
 
     def shapes(self):
-        """Canonical tensor order; linear weights are [in, out] row-major."""
+        """Canonical tensor order; linear weights are [out, in] row-major (y = x W^T + b): the order in which
+        the OPT checkpoints of the paper's experiments (Sec. 7) keep them, hence the order in which Alg. 1's
+        "for each theta_i" meets the elements of a matrix when it draws z."""
         d, f = self.d_model, self.d_ffn
         out = [("embed_tokens", (self.vocab, d)), ("embed_pos", (self.max_pos, d))]
         blk = {"ln1_g": (d,), "ln1_b": (d,), "wq": (d, d), "bq": (d,), "wk": (d, d), "bk": (d,),
                "wv": (d, d), "bv": (d,), "wo": (d, d), "bo": (d,), "ln2_g": (d,), "ln2_b": (d,),
-               "w1": (d, f), "b1": (f,), "w2": (f, d), "b2": (d,)}
+               "w1": (f, d), "b1": (f,), "w2": (d, f), "b2": (d,)}
         for l in range(self.n_layers):
             for name in BLOCK_TENSORS:
                 out.append(("l%d.%s" % (l, name), blk[name]))
@@ -235,14 +237,14 @@ def causal_attention(q, k, v, n_heads):
 def block_forward(h, p, n_heads, ln_eps):
     """One pre-LN decoder block.  `p` maps the names of BLOCK_TENSORS to fp64 arrays."""
     a = layer_norm(h, p["ln1_g"], p["ln1_b"], ln_eps)
-    q = a @ p["wq"] + p["bq"]
-    k = a @ p["wk"] + p["bk"]
-    v = a @ p["wv"] + p["bv"]
+    q = a @ p["wq"].T + p["bq"]
+    k = a @ p["wk"].T + p["bk"]
+    v = a @ p["wv"].T + p["bv"]
     o = causal_attention(q, k, v, n_heads)
-    h = h + o @ p["wo"] + p["bo"]
+    h = h + o @ p["wo"].T + p["bo"]
     f = layer_norm(h, p["ln2_g"], p["ln2_b"], ln_eps)
-    f = np.maximum(f @ p["w1"] + p["b1"], 0.0)
-    return h + f @ p["w2"] + p["b2"]
+    f = np.maximum(f @ p["w1"].T + p["b1"], 0.0)
+    return h + f @ p["w2"].T + p["b2"]
 
 
 def head_logits(h, lnf_g, lnf_b, w_tok, ln_eps):

@@ -26,8 +26,8 @@ def test_shapes_agree_with_input_module():
 
 def test_logits_match_transformers_opt_class():
     """The `transformers` OPT decoder (an independent implementation of the same
-    architecture) given our weights: linear weights transposed to its [out, in]
-    layout and positions shifted by its two reserved rows."""
+    architecture) given our weights: linear weights as they are (its layout is
+    [out, in] too) and positions shifted by its two reserved rows."""
     torch = pytest.importorskip("torch")
     tr = pytest.importorskip("transformers")
     cfg = _cfg(n_layers=2, d=32, h=4, f=64, v=50, p=16)
@@ -49,10 +49,10 @@ def test_logits_match_transformers_opt_class():
             layer.self_attn_layer_norm.weight.copy_(T(p["ln1_g"])); layer.self_attn_layer_norm.bias.copy_(T(p["ln1_b"]))
             for name, wn, bn in (("q_proj", "wq", "bq"), ("k_proj", "wk", "bk"), ("v_proj", "wv", "bv"), ("out_proj", "wo", "bo")):
                 lin = getattr(layer.self_attn, name)
-                lin.weight.copy_(T(p[wn].T)); lin.bias.copy_(T(p[bn]))
+                lin.weight.copy_(T(p[wn])); lin.bias.copy_(T(p[bn]))
             layer.final_layer_norm.weight.copy_(T(p["ln2_g"])); layer.final_layer_norm.bias.copy_(T(p["ln2_b"]))
-            layer.fc1.weight.copy_(T(p["w1"].T)); layer.fc1.bias.copy_(T(p["b1"]))
-            layer.fc2.weight.copy_(T(p["w2"].T)); layer.fc2.bias.copy_(T(p["b2"]))
+            layer.fc1.weight.copy_(T(p["w1"])); layer.fc1.bias.copy_(T(p["b1"]))
+            layer.fc2.weight.copy_(T(p["w2"])); layer.fc2.bias.copy_(T(p["b2"]))
         g_id, b_id = cfg.head_ids()
         dec.final_layer_norm.weight.copy_(T(w[g_id])); dec.final_layer_norm.bias.copy_(T(w[b_id]))
         model.lm_head.weight = dec.embed_tokens.weight
@@ -131,7 +131,8 @@ def test_softmax_scale_and_head_split():
     h = rng.standard_normal((1, 5, 24))
     ln = lambda x, g, b: (x - x.mean(-1, keepdims=True)) / np.sqrt(x.var(-1, keepdims=True) + cfg.ln_eps) * g + b
     a = ln(h[0], p["ln1_g"], p["ln1_b"])
-    q, k, v = a @ p["wq"] + p["bq"], a @ p["wk"] + p["bk"], a @ p["wv"] + p["bv"]
+    lin = lambda x, wgt, b: np.einsum("ti,oi->to", x, wgt) + b            # y[t, o] = sum_i x[t, i] W[o, i] + b[o]
+    q, k, v = lin(a, p["wq"], p["bq"]), lin(a, p["wk"], p["bk"]), lin(a, p["wv"], p["bv"])
     o = np.zeros((5, 24))
     for head in range(3):
         sl = slice(8 * head, 8 * head + 8)
@@ -139,8 +140,8 @@ def test_softmax_scale_and_head_split():
             sc = np.array([q[t, sl] @ k[u, sl] / np.sqrt(8.0) for u in range(t + 1)])
             pr = np.exp(sc - sc.max()); pr /= pr.sum()
             o[t, sl] = sum(pr[u] * v[u, sl] for u in range(t + 1))
-    h1 = h[0] + o @ p["wo"] + p["bo"]
-    f = np.maximum(ln(h1, p["ln2_g"], p["ln2_b"]) @ p["w1"] + p["b1"], 0)
-    want = h1 + f @ p["w2"] + p["b2"]
+    h1 = h[0] + lin(o, p["wo"], p["bo"])
+    f = np.maximum(lin(ln(h1, p["ln2_g"], p["ln2_b"]), p["w1"], p["b1"]), 0)
+    want = h1 + lin(f, p["w2"], p["b2"])
     got = zo.block_forward(h, p, 3, cfg.ln_eps)[0]
     assert np.allclose(got, want, rtol=0, atol=1e-12)

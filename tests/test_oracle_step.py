@@ -93,11 +93,11 @@ def test_g_against_autograd_on_the_tiny_config():
         p = dict(zip(zo.BLOCK_TENSORS, [ws[i] for i in cfg.block_ids(l)]))
         a = F.layer_norm(h, (d,), p["ln1_g"], p["ln1_b"], cfg.ln_eps)
         split = lambda x: x.view(-1, S, H, d // H).transpose(1, 2)
-        q, k, v = split(a @ p["wq"] + p["bq"]), split(a @ p["wk"] + p["bk"]), split(a @ p["wv"] + p["bv"])
+        q, k, v = split(a @ p["wq"].T + p["bq"]), split(a @ p["wk"].T + p["bk"]), split(a @ p["wv"].T + p["bv"])
         o = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(-1, S, d)
-        h = h + o @ p["wo"] + p["bo"]
+        h = h + o @ p["wo"].T + p["bo"]
         f = F.layer_norm(h, (d,), p["ln2_g"], p["ln2_b"], cfg.ln_eps)
-        h = h + torch.relu(f @ p["w1"] + p["b1"]) @ p["w2"] + p["b2"]
+        h = h + torch.relu(f @ p["w1"].T + p["b1"]) @ p["w2"].T + p["b2"]
     g_id, b_id = cfg.head_ids()
     logits = F.layer_norm(h, (d,), ws[g_id], ws[b_id], cfg.ln_eps) @ ws[0].T
     loss = F.cross_entropy(logits[:, :-1].reshape(-1, cfg.vocab), tok[:, 1:].reshape(-1))

@@ -29,11 +29,12 @@ CONFIGS = {
 
 def tensor_shapes(n_layers, d_model, d_ffn, vocab, max_pos):
     """Canonical order: token embedding, position embedding, 16 tensors per
-    block, final LayerNorm gain and bias.  Linear weights are [in, out]."""
+    block, final LayerNorm gain and bias.  Linear weights are [out, in]
+    (y = x W^T + b), the storage order of the OPT checkpoints the paper fine-tunes."""
     d, f = d_model, d_ffn
     blk = {"ln1_g": (d,), "ln1_b": (d,), "wq": (d, d), "bq": (d,), "wk": (d, d), "bk": (d,),
            "wv": (d, d), "bv": (d,), "wo": (d, d), "bo": (d,), "ln2_g": (d,), "ln2_b": (d,),
-           "w1": (d, f), "b1": (f,), "w2": (f, d), "b2": (d,)}
+           "w1": (f, d), "b1": (f,), "w2": (d, f), "b2": (d,)}
     out = [("embed_tokens", (vocab, d)), ("embed_pos", (max_pos, d))]
     for l in range(n_layers):
         out += [("l%d.%s" % (l, n), blk[n]) for n in BLOCK_TENSORS]
