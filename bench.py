@@ -45,7 +45,7 @@ def parse():
                          "the paper's schedule)")
     ap.add_argument("--stochastic-update", action="store_true",
                     help="round the update of Eq. 2 stochastically into the 16-bit storage type (opt-in variant)")
-    ap.add_argument("--update", default="immediate", choices=["deferred", "immediate"],
+    ap.add_argument("--update", default="deferred", choices=["deferred", "immediate"],
                     help="resident fused mode: 'deferred' applies a step's update inside the next step's staging pass (Alg. 2's "
                          "order; the last one is flushed inside the timed region), 'immediate' in a pass of its own at the end "
                          "of the step; theta ends up bit-identical either way")

@@ -29,10 +29,11 @@
  *     1  embed_pos    [max_pos, d_model]   (row t serves position t)
  *     2 + 16*l + k, k = 0..15, for block l:
  *        ln1_g[d] ln1_b[d] wq[d,d] bq[d] wk[d,d] bk[d] wv[d,d] bv[d] wo[d,d] bo[d]
- *        ln2_g[d] ln2_b[d] w1[d,ffn] b1[ffn] w2[ffn,d] b2[d]
+ *        ln2_g[d] ln2_b[d] w1[ffn,d] b1[ffn] w2[d,ffn] b2[d]
  *     2 + 16*L, 3 + 16*L: final LayerNorm gain and bias.
- *   Linear weights are row-major [in, out]:  y = x W + b.  All tensors are
- *   contiguous and stored in cfg.dtype.
+ *   Linear weights are row-major [out, in]:  y = x W^T + b, the order in which
+ *   the OPT checkpoints of the paper's experiments (Sec. 7) keep them.  All
+ *   tensors are contiguous and stored in cfg.dtype.
  *
  * The random direction (what "the same seed gives the same z" means here):
  *   z of element i of tensor t under seed s is word-pair (i%4)/2 of

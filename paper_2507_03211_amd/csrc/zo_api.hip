@@ -52,21 +52,22 @@ enum SlotState { SLOT_EMPTY, SLOT_UPLOADED, SLOT_COMPUTED };
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 // Element offsets of the 16 tensors inside a block as stored (canonical order), and of the
-// staged (transposed, q|k|v fused) copies the forward reads.
+// staged (q|k|v fused, weights next to each other) copies the forward reads.  A linear weight is stored
+// [out, in], which is the K-contiguous layout the GEMMs take, so staging moves no element out of its row.
 struct BlockLayout {
     size_t src_off[kPerBlock];   // in elements, canonical storage order
     uint32_t rows[kPerBlock], cols[kPerBlock];
     size_t total;                // elements per block
-    // staged layout (elements): ln1_g, ln1_b, wqkv_t[3d,d], bqkv[3d], wo_t[d,d], bo, ln2_g, ln2_b, w1_t[F,d], b1, w2_t[d,F], b2
+    // staged layout (elements): ln1_g, ln1_b, wqkv[3d,d], bqkv[3d], wo[d,d], bo, ln2_g, ln2_b, w1[F,d], b1, w2[d,F], b2
     size_t st_ln1g, st_ln1b, st_wqkv, st_bqkv, st_wo, st_bo, st_ln2g, st_ln2b, st_w1, st_b1, st_w2, st_b2;
 };
 
 BlockLayout make_layout(int d, int f)
 {
     BlockLayout L{};
-    const uint32_t r[kPerBlock] = {1, 1, (uint32_t)d, 1, (uint32_t)d, 1, (uint32_t)d, 1, (uint32_t)d, 1, 1, 1, (uint32_t)d, 1, (uint32_t)f, 1};
+    const uint32_t r[kPerBlock] = {1, 1, (uint32_t)d, 1, (uint32_t)d, 1, (uint32_t)d, 1, (uint32_t)d, 1, 1, 1, (uint32_t)f, 1, (uint32_t)d, 1};
     const uint32_t c[kPerBlock] = {(uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d,
-                                   (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)f, (uint32_t)f, (uint32_t)d, (uint32_t)d};
+                                   (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)d, (uint32_t)f, (uint32_t)f, (uint32_t)d};
     size_t off = 0;
     for (int i = 0; i < kPerBlock; ++i) {
         L.rows[i] = r[i]; L.cols[i] = c[i]; L.src_off[i] = off; off += (size_t)r[i] * c[i];
@@ -336,17 +337,17 @@ int stage_block(zo_model *m, int layer, const char *slot_base, uint64_t seed, fl
     char *sp = m->ws + m->wsp.stage[0], *sm = m->ws + m->wsp.stage[1];
     const int t0 = 2 + kPerBlock * layer;
     StageBatch b{};
-    auto add = [&](int k, size_t dst_off, bool tr) {
+    auto add = [&](int k, size_t dst_off) {
         const void *src = slot_base ? (const void *)(slot_base + L.src_off[k] * e) : (const void *)m->tptr[t0 + k];
-        stage_batch_add(b, src, sp + dst_off * e, sm + dst_off * e, L.rows[k], L.cols[k], t0 + k, tr);
+        stage_batch_add(b, src, sp + dst_off * e, sm + dst_off * e, L.rows[k], L.cols[k], t0 + k, false);
     };
-    add(T_LN1G, L.st_ln1g, false); add(T_LN1B, L.st_ln1b, false);
-    add(T_WQ, L.st_wqkv, true); add(T_WK, L.st_wqkv + D * D, true); add(T_WV, L.st_wqkv + 2 * D * D, true);
-    add(T_BQ, L.st_bqkv, false); add(T_BK, L.st_bqkv + D, false); add(T_BV, L.st_bqkv + 2 * D, false);
-    add(T_WO, L.st_wo, true); add(T_BO, L.st_bo, false);
-    add(T_LN2G, L.st_ln2g, false); add(T_LN2B, L.st_ln2b, false);
-    add(T_W1, L.st_w1, true); add(T_B1, L.st_b1, false);
-    add(T_W2, L.st_w2, true); add(T_B2, L.st_b2, false);
+    add(T_LN1G, L.st_ln1g); add(T_LN1B, L.st_ln1b);
+    add(T_WQ, L.st_wqkv); add(T_WK, L.st_wqkv + D * D); add(T_WV, L.st_wqkv + 2 * D * D);
+    add(T_BQ, L.st_bqkv); add(T_BK, L.st_bqkv + D); add(T_BV, L.st_bqkv + 2 * D);
+    add(T_WO, L.st_wo); add(T_BO, L.st_bo);
+    add(T_LN2G, L.st_ln2g); add(T_LN2B, L.st_ln2b);
+    add(T_W1, L.st_w1); add(T_B1, L.st_b1);
+    add(T_W2, L.st_w2); add(T_B2, L.st_b2);
     ZO_PROF(m, K_STAGE, (single ? 2.0 : upd_mode ? 4.0 : 3.0) * e * (double)L.total,
             launch_stage(b, c.dtype, seed, eps, single, m->compute, upd_mode, m->pend_seed[0], m->s_pend));
     return ZO_OK;

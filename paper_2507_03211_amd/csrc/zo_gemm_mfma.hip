@@ -28,6 +28,9 @@ namespace zo {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: arrays of it stay in registers
 
@@ -490,9 +493,10 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
                         bvals[tn][g][3] = Prec<DT>::w2f((uint16_t)(hi >> 16));
                     }
             }
-            // Residual epilogue: the 8 reads of the running sum that a pass needs are all issued one pass ahead,
-            // so a tile pays the memory latency once and not once per row group (a load may not overtake an
-            // earlier store that the compiler cannot tell apart from it).
+            // Residual epilogue: the 8 reads of the running sum that a pass needs are all issued one pass ahead
+            // (a load may not overtake an earlier store that the compiler cannot tell apart from it).  Reading
+            // further ahead (two passes, which is what the registers allow) changes nothing: what the tile waits
+            // for is the bandwidth of all workgroups' read-modify-write bursts arriving together, not one latency.
             float4 hres[2][8];
             auto load_res = [&](int pass, float4 (&h)[8]) {
 #pragma unroll
@@ -536,9 +540,15 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
                             }
                             const int run = tn * 8 + 2 * g + fh;         // which run of 4 columns (0..31) of the row
                             if constexpr (kOut16) {
+                                // two outputs per conversion instruction (round to nearest even, as the single one does)
+                                auto pack2 = [](float lo, float hi) {
+                                    const f32x2 pr = {lo, hi};
+                                    if constexpr (DT == kBF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+                                    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, f16x2));
+                                };
                                 uint2 o;
-                                o.x = (uint32_t)Prec<DT>::acc2a(v[0]) | ((uint32_t)Prec<DT>::acc2a(v[1]) << 16);
-                                o.y = (uint32_t)Prec<DT>::acc2a(v[2]) | ((uint32_t)Prec<DT>::acc2a(v[3]) << 16);
+                                o.x = pack2(v[0], v[1]);
+                                o.y = pack2(v[2], v[3]);
                                 *(uint2 *)(stage + fr * 256 + ((run ^ fr) << 3)) = o;      // 8-byte slots, XOR by the row
                             } else {
                                 *(float4 *)(stage + (fr & 15) * 512 + ((run ^ (fr & 15)) << 4)) = float4{v[0], v[1], v[2], v[3]};

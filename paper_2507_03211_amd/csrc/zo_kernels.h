@@ -33,7 +33,7 @@ struct StageDesc {           // one tensor of an out-of-place W+- staging pass
 constexpr int kStageMaxDesc = 16;
 struct StageBatch { StageDesc d[kStageMaxDesc]; int n; uint32_t total_tiles; };
 constexpr uint32_t kStageTile = 64;          // transposing tile edge
-constexpr uint32_t kStageFlatTile = 4096;    // elements per workgroup when not transposing
+constexpr uint32_t kStageFlatTile = 8192;    // consecutive elements per tile when not transposing
 
 hipError_t launch_z(float *out, uint64_t n, uint64_t seed, uint32_t tid, uint64_t first, hipStream_t s);
 hipError_t launch_normal_pairs(const uint32_t *words, float *z, uint64_t n_pairs, hipStream_t s);

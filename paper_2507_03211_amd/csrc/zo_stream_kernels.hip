@@ -313,9 +313,9 @@ __global__ __launch_bounds__(kStreamThreads) void axpy_z_multi_kernel(const Tens
 }
 
 // ------------------------------------------------------------------ staging W+ / W-
-// Flat tiles copy kStageFlatTile consecutive elements; transposing tiles move a 64 x 64 patch
-// of a [rows, cols] matrix through LDS so that both the read (along cols) and the write
-// (along rows of the transposed result) are coalesced.
+// Transposing form (a caller that keeps a matrix [in, out] and wants the GEMMs' [out, in]): tiles move a 64 x 64
+// patch of a [rows, cols] matrix through LDS so that both the read (along cols) and the write (along rows of the
+// transposed result) are coalesced.  Tensors that keep their layout go through stage_flat_kernel below.
 // UPD != 0: the pass first applies a pending update of Eq. 2 to theta itself, theta <- rn(fma(s, z', theta)) with z'
 // drawn from `upd_seed` and s read from dev_scale (UPD 1: round to nearest, 2: stochastic rounding), writes theta
 // back, and stages W+- from the updated value: Alg. 2's deferred update, in the pass that reads theta anyway.  The
@@ -331,7 +331,7 @@ constexpr int kStageThreads = ZO_STAGE_THREADS;       // groups of 256 threads, 
 // persistent loop each group takes one tile (group g of workgroup w: tiles (w + i gridDim.x) G + g).  A transposing
 // tile goes through the group's LDS buffer one sign at a time (W+ out, then W-), which halves the buffer and lets
 // two 1024-thread workgroups, all 32 wave slots, share a CU next to the 24 KiB table.  The barriers of a round are
-// the same for every group whatever its tile is (flat, transposing or none).
+// the same for every group whether it has a tile or not.
 template <int DT, bool SINGLE, int UPD>
 __global__ __launch_bounds__(kStageThreads) __attribute__((amdgpu_waves_per_eu((DT != kFP32 && UPD != 2) ? 8 : 4))) void stage_kernel(StageBatch batch, uint64_t seed, float eps, uint64_t upd_seed,
                                                               const float *__restrict__ dev_scale)
@@ -366,70 +366,7 @@ __global__ __launch_bounds__(kStageThreads) __attribute__((amdgpu_waves_per_eu((
         const W *src = theta;
         W *__restrict__ dp = (W *)d.dst_plus;
         W *__restrict__ dm = (W *)d.dst_minus;
-        const uint64_t numel = (uint64_t)d.rows * d.cols;
-        const bool transposing = active && d.transpose != 0;
-
-        if (active && !d.transpose) {
-            constexpr int kIter = kStageFlatTile / (256 * VN);
-#pragma unroll
-            for (int it = 0; it < kIter; ++it) {
-                const uint64_t i0 = (uint64_t)tile * kStageFlatTile + (uint64_t)(it * 256 + tix) * VN;
-                if (i0 >= numel) break;
-                float z[VN];
-                if constexpr (!SINGLE) {
-#pragma unroll
-                    for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, d.tid, i0 / 4 + b), z + 4 * b, ln_tab);
-                }
-                const bool whole = i0 + VN <= numel;
-                if constexpr (SINGLE) {
-                    if (whole) *(uint4 *)(dp + i0) = *(const uint4 *)(src + i0);
-                    else for (int e = 0; e < VN && i0 + e < numel; ++e) dp[i0 + e] = src[i0 + e];
-                } else {
-                    float th[VN], a[VN], b[VN];
-                    if (whole) {
-                        unpack16<DT>(*(const uint4 *)(src + i0), th);
-                    } else {
-                        for (int e = 0; e < VN; ++e) th[e] = i0 + e < numel ? Prec<DT>::w2f(src[i0 + e]) : 0.0f;
-                    }
-                    if constexpr (UPD != 0) {
-                        float zu[VN];
-#pragma unroll
-                        for (int bk = 0; bk < VN / 4; ++bk) normal4(philox_block(upd_seed, d.tid, i0 / 4 + bk), zu + 4 * bk, ln_tab);
-#pragma unroll
-                        for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(us, zu[e], th[e]);
-                        uint4 stored;
-                        if constexpr (UPD == 2) {
-                            uint32_t rw[VN];
-#pragma unroll
-                            for (int bk = 0; bk < VN / 4; ++bk) {
-                                const u32x4 r = philox_block(upd_seed, d.tid, i0 / 4 + bk, 3u);
-                                rw[4 * bk] = r.x; rw[4 * bk + 1] = r.y; rw[4 * bk + 2] = r.z; rw[4 * bk + 3] = r.w;
-                            }
-                            stored = pack16_sr<DT>(th, rw);
-                        } else {
-                            stored = pack16<DT>(th);
-                        }
-                        unpack16<DT>(stored, th);          // staging starts from the stored value
-                        if (whole) *(uint4 *)(theta + i0) = stored;
-                        else for (int e = 0; e < VN && i0 + e < numel; ++e) theta[i0 + e] = Prec<DT>::f2w(th[e]);   // exact
-                    }
-#pragma unroll
-                    for (int e = 0; e < VN; ++e) {
-                        a[e] = __builtin_fmaf(eps, z[e], th[e]);
-                        b[e] = __builtin_fmaf(-eps, z[e], th[e]);
-                    }
-                    if (whole) {
-                        *(uint4 *)(dp + i0) = pack16<DT>(a);
-                        *(uint4 *)(dm + i0) = pack16<DT>(b);
-                    } else {
-                        for (int e = 0; e < VN && i0 + e < numel; ++e) {
-                            dp[i0 + e] = Prec<DT>::f2w(a[e]);
-                            dm[i0 + e] = Prec<DT>::f2w(b[e]);
-                        }
-                    }
-                }
-            }
-        }
+        const bool transposing = active;          // the launcher sends flat tensors to stage_flat_kernel
 
         // transposing tile: rows r0.., cols c0..  (cols % 4 == 0 is guaranteed by the caller)
         // A thread owns a 4 x 4 patch (4 adjacent rows, one Philox block each), so each of its 4 columns goes
@@ -556,6 +493,135 @@ __global__ __launch_bounds__(kStageThreads) __attribute__((amdgpu_waves_per_eu((
             if (transposing) tile_out(dm);
         }
         __syncthreads();        // the tile is read out before the next round writes it
+    }
+}
+
+// ------------------------------------------------------------------ staging W+ / W-, nothing to transpose
+// The batch of a decoder block: every tensor keeps its layout (a linear weight is stored [out, in], the layout
+// the GEMMs read), so the pass is a plain stream, theta in, W+ and W- out, built like axpy_z_kernel: four
+// 512-thread workgroups per CU that fill the radius table once, chunks of kStageFlatTile consecutive elements of
+// one tensor, the next chunk's theta fetched into registers while this one is computed.  Chunk numbering and
+// arithmetic are those of stage_kernel's flat tiles.
+template <int DT, bool SINGLE, int UPD>
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu((DT != kFP32 && UPD == 0) ? 8 : 4)))
+void stage_flat_kernel(StageBatch batch, uint64_t seed, float eps, uint64_t upd_seed,
+                                                                    const float *__restrict__ dev_scale)
+{
+    using W = typename Prec<DT>::W;
+    constexpr int VN = Vec16<DT>::N;
+    constexpr int kIter = kStageFlatTile / (kStreamThreads * VN);
+    static_assert(kIter >= 1 && kIter * kStreamThreads * VN == (int)kStageFlatTile, "a chunk is a whole number of 16-byte pieces per thread");
+    static_assert(!(SINGLE && UPD != 0) && !(DT == kFP32 && UPD == 2), "no such variant");
+    __shared__ float4 ln_tab[SINGLE ? 1 : kRayleighLast];
+    if constexpr (!SINGLE) load_rayleigh_cells(ln_tab);
+    float us = 0.0f;
+    if constexpr (UPD != 0) us = *dev_scale;
+    struct Piece {
+        W *theta, *dp, *dm;      // theta is written only when UPD != 0
+        uint64_t numel, base;    // base: first element of the chunk in its tensor
+        uint32_t tid;
+        bool whole;              // the chunk lies wholly inside the tensor
+    };
+    int di = 0;
+    auto piece_of = [&](uint32_t tile) {
+        while (di + 1 < batch.n && batch.d[di + 1].first_tile <= tile) ++di;
+        const StageDesc &d = batch.d[di];
+        Piece p;
+        p.theta = (W *)const_cast<void *>(d.src); p.dp = (W *)d.dst_plus; p.dm = (W *)d.dst_minus;
+        p.numel = (uint64_t)d.rows * d.cols;
+        p.base = (uint64_t)(tile - d.first_tile) * kStageFlatTile;
+        p.tid = d.tid;
+        p.whole = p.base + kStageFlatTile <= p.numel;
+        return p;
+    };
+    auto load_chunk = [&](const Piece &p, uint4 (&v)[kIter]) {
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) v[it] = *(const uint4 *)(p.theta + p.base + (size_t)(it * kStreamThreads + threadIdx.x) * VN);
+    };
+    // 16 bytes of theta at element i0 (`raw` when `full`, else the tensor's ragged tail, read element-wise)
+    auto piece16 = [&](const Piece &p, uint64_t i0, const uint4 &raw, bool full) {
+        if constexpr (SINGLE) {
+            if (full) *(uint4 *)(p.dp + i0) = raw;
+            else for (int e = 0; e < VN && i0 + e < p.numel; ++e) p.dp[i0 + e] = p.theta[i0 + e];
+        } else {
+            float z[VN];
+#pragma unroll
+            for (int b = 0; b < VN / 4; ++b) normal4(philox_block(seed, p.tid, i0 / 4 + b), z + 4 * b, ln_tab);
+            float th[VN], a[VN], b[VN];
+            if (full) {
+                unpack16<DT>(raw, th);
+            } else {
+                for (int e = 0; e < VN; ++e) th[e] = i0 + e < p.numel ? Prec<DT>::w2f(p.theta[i0 + e]) : 0.0f;
+            }
+            if constexpr (UPD != 0) {
+                float zu[VN];
+#pragma unroll
+                for (int bk = 0; bk < VN / 4; ++bk) normal4(philox_block(upd_seed, p.tid, i0 / 4 + bk), zu + 4 * bk, ln_tab);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) th[e] = __builtin_fmaf(us, zu[e], th[e]);
+                uint4 stored;
+                if constexpr (UPD == 2) {
+                    uint32_t rw[VN];
+#pragma unroll
+                    for (int bk = 0; bk < VN / 4; ++bk) {
+                        const u32x4 r = philox_block(upd_seed, p.tid, i0 / 4 + bk, 3u);
+                        rw[4 * bk] = r.x; rw[4 * bk + 1] = r.y; rw[4 * bk + 2] = r.z; rw[4 * bk + 3] = r.w;
+                    }
+                    stored = pack16_sr<DT>(th, rw);
+                } else {
+                    stored = pack16<DT>(th);
+                }
+                unpack16<DT>(stored, th);          // staging starts from the stored value
+                if (full) *(uint4 *)(p.theta + i0) = stored;
+                else for (int e = 0; e < VN && i0 + e < p.numel; ++e) p.theta[i0 + e] = Prec<DT>::f2w(th[e]);   // exact
+            }
+#pragma unroll
+            for (int e = 0; e < VN; ++e) {
+                a[e] = __builtin_fmaf(eps, z[e], th[e]);
+                b[e] = __builtin_fmaf(-eps, z[e], th[e]);
+            }
+            if (full) {
+                *(uint4 *)(p.dp + i0) = pack16<DT>(a);
+                *(uint4 *)(p.dm + i0) = pack16<DT>(b);
+            } else {
+                for (int e = 0; e < VN && i0 + e < p.numel; ++e) {
+                    p.dp[i0 + e] = Prec<DT>::f2w(a[e]);
+                    p.dm[i0 + e] = Prec<DT>::f2w(b[e]);
+                }
+            }
+        }
+    };
+    uint32_t c = blockIdx.x;
+    if (c >= batch.total_tiles) return;
+    Piece p = piece_of(c);
+    uint4 cur[kIter], nxt[kIter];
+    if (p.whole) load_chunk(p, cur);
+    for (;;) {
+        const uint32_t cn = c + gridDim.x;
+        const bool has_next = cn < batch.total_tiles;
+        Piece pn = p;
+        if (has_next) {
+            pn = piece_of(cn);
+            if (pn.whole) load_chunk(pn, nxt);
+        }
+        if (p.whole) {
+#pragma unroll
+            for (int it = 0; it < kIter; ++it) piece16(p, p.base + (uint64_t)(it * kStreamThreads + threadIdx.x) * VN, cur[it], true);
+        } else {
+#pragma unroll 1
+            for (int it = 0; it < kIter; ++it) {
+                const uint64_t i0 = p.base + (uint64_t)(it * kStreamThreads + threadIdx.x) * VN;
+                if (i0 >= p.numel) break;
+                const bool full = i0 + VN <= p.numel;
+                uint4 raw = uint4{0u, 0u, 0u, 0u};
+                if (full) raw = *(const uint4 *)(p.theta + i0);
+                piece16(p, i0, raw, full);
+            }
+        }
+        if (!has_next) break;
+        c = cn; p = pn;
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) cur[it] = nxt[it];
     }
 }
 
@@ -692,9 +758,38 @@ hipError_t launch_stage(const StageBatch &b, int dtype, uint64_t seed, float eps
     if (b.total_tiles == 0) return hipSuccess;
     if (upd_mode < 0 || upd_mode > 2 || (upd_mode != 0 && (single_copy || !dev_scale)) || (upd_mode == 2 && dtype == kFP32))
         return hipErrorInvalidValue;
+    // tensors that keep their layout and tensors to transpose take different kernels: split a mixed batch
+    StageBatch flat{}, tr{};
+    for (int i = 0; i < b.n; ++i) {
+        const StageDesc &d = b.d[i];
+        stage_batch_add(d.transpose ? tr : flat, d.src, d.dst_plus, d.dst_minus, d.rows, d.cols, d.tid, d.transpose != 0);
+    }
+    if (flat.n != 0 && tr.n != 0) {
+        if (hipError_t e = launch_stage(flat, dtype, seed, eps, single_copy, s, upd_mode, upd_seed, dev_scale); e != hipSuccess) return e;
+        return launch_stage(tr, dtype, seed, eps, single_copy, s, upd_mode, upd_seed, dev_scale);
+    }
+    unsigned g = 0;
+    if (tr.n == 0) {
+        // registers allow four workgroups per CU for the plain 16-bit pass, three with the update folded in, two in fp32
+        const int per_cu = dtype == kFP32 ? 2 : upd_mode != 0 ? 3 : ZO_AXPY_PER_CU;
+        if (hipError_t e = persistent_grid(b.total_tiles, per_cu, &g); e != hipSuccess) return e;
+        const dim3 grid(g), block(kStreamThreads);
+#define ZO_STAGE(DT)                                                                                                   \
+    if (single_copy) stage_flat_kernel<DT, true, 0><<<grid, block, 0, s>>>(b, seed, eps, 0, nullptr);                   \
+    else if (upd_mode == 0) stage_flat_kernel<DT, false, 0><<<grid, block, 0, s>>>(b, seed, eps, 0, nullptr);           \
+    else if (upd_mode == 1) stage_flat_kernel<DT, false, 1><<<grid, block, 0, s>>>(b, seed, eps, upd_seed, dev_scale);  \
+    else if constexpr (DT != kFP32) stage_flat_kernel<DT, false, 2><<<grid, block, 0, s>>>(b, seed, eps, upd_seed, dev_scale); \
+    return hipGetLastError();
+        switch (dtype) {
+        case kFP32: ZO_STAGE(kFP32)
+        case kBF16: ZO_STAGE(kBF16)
+        case kFP16: ZO_STAGE(kFP16)
+        }
+#undef ZO_STAGE
+        return hipErrorInvalidValue;
+    }
     // LDS per workgroup of four groups: 58 KiB (16-bit types), 92 KiB (fp32), 34 / 68 KiB for the plain copy
     constexpr int G = kStageThreads / 256;
-    unsigned g = 0;
     if (hipError_t e = persistent_grid((b.total_tiles + G - 1) / G, dtype == kFP32 ? 1 : ZO_STAGE_PER_CU, &g); e != hipSuccess) return e;
     const dim3 grid(g), block(kStageThreads);
 #define ZO_STAGE(DT)                                                                                              \
