@@ -329,7 +329,7 @@ int stage_globals(zo_model *m, int seq, uint64_t seed, float eps, int upd_mode)
 // Stage one block into the per-sign scratch.  `slot_base` == nullptr: the block's 16 tensors are read
 // where the caller keeps them (resident model, separately allocated); otherwise from a device copy of
 // the block laid out contiguously in canonical order (streamed model).
-int stage_block(zo_model *m, int layer, const char *slot_base, uint64_t seed, float eps, bool single, int upd_mode = 0)
+int stage_block(zo_model *m, int layer, const char *slot_base, uint64_t seed, float eps, bool single, int upd_mode = 0, int pend = 0)
 {
     const zo_config &c = m->cfg;
     const BlockLayout &L = m->lay;
@@ -349,7 +349,7 @@ int stage_block(zo_model *m, int layer, const char *slot_base, uint64_t seed, fl
     add(T_W1, L.st_w1); add(T_B1, L.st_b1);
     add(T_W2, L.st_w2); add(T_B2, L.st_b2);
     ZO_PROF(m, K_STAGE, (single ? 2.0 : upd_mode ? 4.0 : 3.0) * e * (double)L.total,
-            launch_stage(b, c.dtype, seed, eps, single, m->compute, upd_mode, m->pend_seed[0], m->s_pend));
+            launch_stage(b, c.dtype, seed, eps, single, m->compute, upd_mode, m->pend_seed[pend], m->s_pend + pend));
     return ZO_OK;
 }
 
@@ -527,10 +527,12 @@ int stream_compute(zo_model *m, int block, bool forward, bool force_writeback = 
         // a block that stays in HBM is visited once per step and only ever lacks the newest update (Alg. 2: a
         // module takes last step's update at its visit)
         SpanScope span(m, ZO_SPAN_COMPUTE, block, m->compute);
-        if (m->pend_n > 0)
+        const int sr_mode = m->update_rounding == ZO_ROUND_STOCHASTIC ? 2 : 1;
+        if (m->pend_n > 0 && !forward)
             ZO_TRY(axpy_range(m, 2 + kPerBlock * block, kPerBlock, m->pend_seed[m->pend_n - 1], 0.0f, m->s_pend + (m->pend_n - 1), true));
         if (forward) {
-            ZO_TRY(stage_block(m, block, nullptr, m->step_seed, m->step_eps, false));
+            // the pending update rides on the staging pass, which reads theta anyway
+            ZO_TRY(stage_block(m, block, nullptr, m->step_seed, m->step_eps, false, m->pend_n > 0 ? sr_mode : 0, m->pend_n > 0 ? m->pend_n - 1 : 0));
             ZO_TRY(block_forward(m, 2, m->step_batch, m->step_seq));
         }
         return ZO_OK;
@@ -540,7 +542,8 @@ int stream_compute(zo_model *m, int block, bool forward, bool force_writeback = 
         return fail(ZO_ESTATE, "block %d was not prefetched", block);
     ZO_HIP(hipStreamWaitEvent(m->compute, m->ev_uploaded[slot], 0));
     SpanScope span(m, ZO_SPAN_COMPUTE, block, m->compute);      // from here on: the block's kernels, not the wait for its upload
-    if (m->pend_n == 1) {
+    const bool fold = forward && m->pend_n == 1;     // a single pending update rides on the staging pass
+    if (m->pend_n == 1 && !fold) {
         ZO_TRY(axpy_range(m, 2 + kPerBlock * block, kPerBlock, m->pend_seed[0], 0.0f, m->s_pend, true));
     } else if (m->pend_n > 1) {      // all of them in one pass over the block
         const int first = 2 + kPerBlock * block;
@@ -558,7 +561,9 @@ int stream_compute(zo_model *m, int block, bool forward, bool force_writeback = 
     // the updated copy goes back to the host only in the step that closes a write-back interval (or at a flush);
     // otherwise it is dropped after use and the host copy stays pend_n steps behind
     m->slot_dirty[slot] = m->pend_n > 0 && (m->pend_n >= m->wb_interval || force_writeback);
-    if (forward) ZO_TRY(stage_block(m, block, m->ws + m->wsp.slot[slot], m->step_seed, m->step_eps, false));
+    if (forward)
+        ZO_TRY(stage_block(m, block, m->ws + m->wsp.slot[slot], m->step_seed, m->step_eps, false,
+                           fold ? (m->update_rounding == ZO_ROUND_STOCHASTIC ? 2 : 1) : 0, 0));
     ZO_HIP(hipEventRecord(m->ev_staged[slot], m->compute));
     if (forward) ZO_TRY(block_forward(m, 2, m->step_batch, m->step_seq));
     m->slot_state[slot] = SLOT_COMPUTED;
