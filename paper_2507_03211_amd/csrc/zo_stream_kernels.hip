@@ -758,18 +758,12 @@ hipError_t launch_stage(const StageBatch &b, int dtype, uint64_t seed, float eps
     if (b.total_tiles == 0) return hipSuccess;
     if (upd_mode < 0 || upd_mode > 2 || (upd_mode != 0 && (single_copy || !dev_scale)) || (upd_mode == 2 && dtype == kFP32))
         return hipErrorInvalidValue;
-    // tensors that keep their layout and tensors to transpose take different kernels: split a mixed batch
-    StageBatch flat{}, tr{};
-    for (int i = 0; i < b.n; ++i) {
-        const StageDesc &d = b.d[i];
-        stage_batch_add(d.transpose ? tr : flat, d.src, d.dst_plus, d.dst_minus, d.rows, d.cols, d.tid, d.transpose != 0);
-    }
-    if (flat.n != 0 && tr.n != 0) {
-        if (hipError_t e = launch_stage(flat, dtype, seed, eps, single_copy, s, upd_mode, upd_seed, dev_scale); e != hipSuccess) return e;
-        return launch_stage(tr, dtype, seed, eps, single_copy, s, upd_mode, upd_seed, dev_scale);
-    }
+    // tensors that keep their layout and tensors to transpose take different kernels; no caller mixes them in a batch
+    int n_tr = 0;
+    for (int i = 0; i < b.n; ++i) n_tr += b.d[i].transpose != 0;
+    if (n_tr != 0 && n_tr != b.n) return hipErrorInvalidValue;
     unsigned g = 0;
-    if (tr.n == 0) {
+    if (n_tr == 0) {
         // registers allow four workgroups per CU for the plain 16-bit pass, three with the update folded in, two in fp32
         const int per_cu = dtype == kFP32 ? 2 : upd_mode != 0 ? 3 : ZO_AXPY_PER_CU;
         if (hipError_t e = persistent_grid(b.total_tiles, per_cu, &g); e != hipSuccess) return e;
