@@ -33,6 +33,7 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: arrays of it stay in registers
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -504,7 +505,12 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
                     const int r = 2 * i + (lane >> 5), c = lane & 31;
                     const int mr = m0 + wm * 128 + pass * 16 + r, nc = ncol0 + c * 4;
                     h[i] = float4{0.f, 0.f, 0.f, 0.f};
-                    if (mr < m_half && nc < n) h[i] = *(const float4 *)((const float *)y + ((size_t)sign * m_half + mr) * n + nc);
+                    if (mr < m_half && nc < n) {
+                        // read once, written once: neither the running sum nor any output is worth an L2 line that
+                        // an operand slab could keep (non-temporal loads and stores)
+                        const f32x4 t = __builtin_nontemporal_load((const f32x4 *)((const float *)y + ((size_t)sign * m_half + mr) * n + nc));
+                        h[i] = float4{t.x, t.y, t.z, t.w};
+                    }
                 }
             };
             float bias4[4] = {0.f, 0.f, 0.f, 0.f};
@@ -564,7 +570,7 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
                         uint4 q = *(const uint4 *)(stage + r * 256 + ((c16 ^ (r >> 1)) << 4));
                         if (r & 1) q = uint4{q.z, q.w, q.x, q.y};                    // odd rows hold the two runs swapped
                         const int mr = mbase + r, nc = ncol0 + c16 * 8;
-                        if (mr < m_half && nc < n) *(uint4 *)((uint16_t *)y + ((size_t)sign * m_half + mr) * n + nc) = q;
+                        if (mr < m_half && nc < n) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, q), (u32x4 *)((uint16_t *)y + ((size_t)sign * m_half + mr) * n + nc));
                     }
                 } else {
 #pragma unroll
@@ -577,7 +583,7 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
                             if constexpr (EPI == 2) {
                                 float4 h = hres[pass & 1][i];
                                 h.x += q.x + bias4[0]; h.y += q.y + bias4[1]; h.z += q.z + bias4[2]; h.w += q.w + bias4[3];
-                                *p = h;
+                                __builtin_nontemporal_store(f32x4{h.x, h.y, h.z, h.w}, (f32x4 *)p);
                             } else {
                                 *p = q;
                             }
