@@ -212,3 +212,50 @@ def test_steps_queued_without_host_waits_leave_the_same_bits(lookahead):
     zo_amd.zo_flush_pending(stm.handle)
     assert all(x.tobytes() == y.tobytes() for x, y in zip(res.theta(), stm.theta()))
     res.close(); stm.close()
+
+
+def test_profile_classes_and_alg3_spans_of_a_streamed_step():
+    """zo_profile_*: per-class kernel times and work, and the (upload, kernels, write-back) records of Alg. 3's
+    schedule: one of each per streamed block and step, every block's kernels after its upload, its write-back after
+    its kernels, block i + 1's upload not waiting for block i's kernels to end; profiling changes no result."""
+    L = SHAPE["n_layers"]
+    ref = Model(**SHAPE, dtype=zi.BF16, batch=2, seq=40, seed=3, plain_small=False, std=0.05, streamed=True)
+    stm = Model(**SHAPE, dtype=zi.BF16, batch=2, seq=40, seed=3, plain_small=False, std=0.05, streamed=True, device_blocks=(1,))
+    tok, tok_dev = stm.tokens()
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_profile_end(stm.handle)                               # not begun
+    zo_amd.zo_profile_begin(stm.handle, 4096)
+    with pytest.raises(zo_amd.ZoError):
+        zo_amd.zo_profile_spans(stm.handle)                             # still on
+    got = [zo_amd.zo_step(stm.handle, tok_dev, 2, 40, seed, 1e-3, 1e-2) for seed in (0, 1)]
+    classes = zo_amd.zo_profile_end(stm.handle)
+    spans = zo_amd.zo_profile_spans(stm.handle)
+    want = [zo_amd.zo_step(ref.handle, tok_dev, 2, 40, seed, 1e-3, 1e-2) for seed in (0, 1)]
+    assert got == want
+    # classes: 2 steps x (4 GEMMs per block + the LM head, one launch or one per sign and row chunk), attention and
+    # LayerNorm per block, staging per block + globals
+    assert classes["linear"][1] >= 2 * (4 * L + 1) and classes["attention"][1] == 2 * L
+    assert classes["norm"][1] == 2 * (2 * L + 1) and classes["stage"][1] >= 2 * (L + 1)
+    for name in ("linear", "attention", "stage", "norm"):
+        ms, launches, work = classes[name]
+        assert ms > 0 and work > 0, name
+    M, d, F = 2 * 2 * 40, SHAPE["d_model"], SHAPE["d_ffn"]
+    flop = 2.0 * M * (L * (4 * d * d + 2 * d * F) + d * SHAPE["vocab"])
+    assert abs(classes["linear"][2] / (2 * flop) - 1) < 1e-12          # 2 m n k over every GEMM of the two steps
+    # spans: blocks 0 and 2 stream (upload, kernels, write-back each step), block 1 lives in HBM (kernels only)
+    by = {}
+    for kind, block, t0, t1 in spans:
+        assert 0 <= block < L and t0 >= 0 and t1 >= t0
+        by.setdefault((kind, block), []).append((t0, t1))
+    U, C, O = zo_amd.ZO_SPAN_UPLOAD, zo_amd.ZO_SPAN_COMPUTE, zo_amd.ZO_SPAN_WRITEBACK
+    assert all(len(by[(C, b)]) == 2 for b in range(L))
+    assert (U, 1) not in by and (O, 1) not in by
+    for b in (0, 2):
+        assert len(by[(U, b)]) == 2
+        assert len(by[(O, b)]) >= 1                                     # step 1 has no update to write back yet
+        for (u0, u1), (c0, c1) in zip(by[(U, b)], by[(C, b)]):
+            assert c0 >= u1 - 1e-3                                      # kernels start once the block has landed
+        last_c, last_o = by[(C, b)][-1], by[(O, b)][-1]
+        assert last_o[0] >= last_c[0]                                   # written back after its update was enqueued
+    assert min(t0 for _, _, t0, _ in spans) == 0.0
+    ref.close(); stm.close()
