@@ -89,30 +89,62 @@ __device__ __forceinline__ void epilogue_store(float (&v)[4], const uint16_t *__
 // Argument reuse for this epilogue: bias_p -> int32 target[rows], bias_m -> float target_logit[rows],
 // y -> float2 partial[rows][n_partial].
 template <int TN>
-__device__ __forceinline__ void ce_partial_row(const f32x16 (&a)[TN], int col0, int fh, int n, int tg, float *tgt_logit_row,
-                                               float2 *partial_slot)
+__device__ __forceinline__ void ce_partial_row(const f32x16 (&a)[TN], int col0, int fh, int n, bool live, int tg,
+                                               float *tgt_logit_row, float2 *partial_slot)
 {
-    float mx = -INFINITY;
+    // `live` false: a row past the ragged end of the tile.  It takes part (the two halves of the wave exchange their
+    // results below) and stores nothing; its pointers are those of the last valid row.
+    //
+    // A lane's 16 TN logits in register order k = 16 tn + i sit at columns col0 + 32 tn + 8 (i / 4) + 4 fh + i % 4,
+    // which grow with k.  Nothing here keeps one compare result per element alive (64 of them, the same for every
+    // row block, is what the compiler would hoist and then spill): the ragged strip of the vocabulary is masked by
+    // arithmetic, the target logit is picked by a tree of selects on the bits of its register number.
+    constexpr int NE = 16 * TN;
+    float v[NE];
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn)
+    for (int k = 0; k < NE; ++k) v[k] = a[k / 16][k % 16];
+    if (col0 + 32 * TN > n) {                      // wave-uniform: only the last strip of the vocabulary
+        // number of this lane's registers that lie inside the vocabulary
+        int kmax = 0;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int nc = col0 + tn * 32 + 8 * (i >> 2) + 4 * fh + (i & 3);
-            if (nc < n) mx = a[tn][i] > mx ? a[tn][i] : mx;
+        for (int g = 0; g < 4 * TN; ++g) {         // runs of 4 columns: col0 + 32 (g / 4) + 8 (g % 4) + 4 fh + 0..3
+            const int c0 = col0 + 32 * (g / 4) + 8 * (g % 4) + 4 * fh, left = n - c0;
+            kmax += left < 0 ? 0 : left > 4 ? 4 : left;
         }
+        const float kf = (float)kmax - 0.5f;
+#pragma unroll
+        for (int k = 0; k < NE; ++k) {
+            // (kf - k) * inf is +inf for registers inside, -inf outside (never 0 * inf); min(., 0) makes it 0 or -inf
+            const float pen = __builtin_fminf((kf - (float)k) * INFINITY, 0.0f);
+            v[k] += pen;
+        }
+    }
+    float mx = v[0];
+#pragma unroll
+    for (int k = 1; k < NE; ++k) mx = __builtin_fmaxf(mx, v[k]);
+    const float ms = mx > -INFINITY ? mx : 0.0f;      // a strip that lies wholly past the vocabulary: exp(-inf - 0) = 0
     float sum = 0.0f;
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn)
+    for (int k = 0; k < NE; ++k) sum += __expf(v[k] - ms);
+    // the target column, if it is one of this lane's: register 16 (rel / 32) + 4 (rel / 8 % 4) + rel % 4 of the lane
+    // half rel / 4 % 2
+    const int rel = tg - col0;
+    const bool mine = rel >= 0 && rel < 32 * TN && ((rel >> 2) & 1) == fh;
+    const int which = (rel >> 5) * 16 + ((rel >> 3) & 3) * 4 + (rel & 3);
+    float t[NE];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int nc = col0 + tn * 32 + 8 * (i >> 2) + 4 * fh + (i & 3);
-            if (nc < n) sum += __expf(a[tn][i] - mx);
-            if (nc == tg) *tgt_logit_row = a[tn][i];
-        }
+    for (int k = 0; k < NE; ++k) t[k] = v[k];
+#pragma unroll
+    for (int bit = 0, cnt = NE; cnt > 1; ++bit, cnt >>= 1) {
+        const bool odd = (which >> bit) & 1;
+#pragma unroll
+        for (int k = 0; k < cnt / 2; ++k) t[k] = odd ? t[2 * k + 1] : t[2 * k];
+    }
+    if (live && mine) *tgt_logit_row = t[0];
     const float mo = __shfl_xor(mx, 32, 64), so = __shfl_xor(sum, 32, 64);
     const float m2 = mx > mo ? mx : mo;
     const float s2 = (mx > -INFINITY ? sum * __expf(mx - m2) : 0.0f) + (mo > -INFINITY ? so * __expf(mo - m2) : 0.0f);
-    if (fh == 0) *partial_slot = float2{m2, s2};
+    if (live && fh == 0) *partial_slot = float2{m2, s2};
 }
 
 // LDS tile: [rows][8 chunks] of uint4, chunk c of row r stored at c ^ ((r >> 1) & 7): the LDS has 64
@@ -203,12 +235,8 @@ __global__ __launch_bounds__(256) void linear_mfma_kernel(const uint16_t *__rest
             const int mr = m0 + wm * 64 + tm * 32 + fr;
             const size_t row = (size_t)sign * m_half + (mr < m_half ? mr : m_half - 1);
             const f32x16 a[2] = {acc[0][tm], acc[1][tm]};
-            float dummy_logit;
-            float2 dummy_pair;
-            const bool live = mr < m_half;
-            ce_partial_row<2>(a, n0 + wn * 64, fh, n, live ? ((const int32_t *)b_p)[row] : -1,
-                              live ? (float *)b_m + row : &dummy_logit,
-                              live ? (float2 *)y + row * n_partial + (blockIdx.x * 2 + wn) : &dummy_pair);
+            ce_partial_row<2>(a, n0 + wn * 64, fh, n, mr < m_half, ((const int32_t *)b_p)[row], (float *)b_m + row,
+                              (float2 *)y + row * n_partial + (blockIdx.x * 2 + wn));
         }
         return;
     }
@@ -450,12 +478,8 @@ __global__ __launch_bounds__(256) void linear_mfma256_kernel(const uint16_t *__r
                 const int mr = m0 + wm * 128 + tm * 32 + fr;
                 const size_t row = (size_t)sign * m_half + (mr < m_half ? mr : m_half - 1);
                 const f32x16 a[4] = {acc[0][tm], acc[1][tm], acc[2][tm], acc[3][tm]};
-                float dummy_logit;
-                float2 dummy_pair;
-                const bool live = mr < m_half;
-                ce_partial_row<4>(a, n0 + wn * 128, fh, n, live ? ((const int32_t *)b_p)[row] : -1,
-                                  live ? (float *)b_m + row : &dummy_logit,
-                                  live ? (float2 *)y + row * n_partial + (cur.tcol * 2 + wn) : &dummy_pair);
+                ce_partial_row<4>(a, n0 + wn * 128, fh, n, mr < m_half, ((const int32_t *)b_p)[row], (float *)b_m + row,
+                                  (float2 *)y + row * n_partial + (cur.tcol * 2 + wn));
             }
         } else {
             // Output through LDS so that global stores are whole rows: in the MFMA layout a lane holds runs of 4
