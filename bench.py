@@ -236,6 +236,8 @@ def main():
               "No figure for %d GPUs exists." % args.gpus, file=sys.stderr)
         sys.exit(2)
     import torch
+    from paper_2507_03211_amd.build import ensure_built
+    ensure_built()                      # loads what is built, compiles only when nothing is
     import paper_2507_03211_amd as zo_amd
     import zo_inputs as zi
 

@@ -53,5 +53,11 @@ def build(verbose=False):
     return LIB
 
 
+def ensure_built():
+    """Build only when no library is there (tests, the smoke run and the bench call this; the binding itself never
+    builds: it raises when the library is missing)."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))

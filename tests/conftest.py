@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    # load what is built; compile only when nothing is (hipcc cross-compiles gfx950 without a GPU)
+    from paper_2507_03211_amd.build import ensure_built
+    ensure_built()
+
+
 def _has_gpu():
     try:
         import torch
