@@ -68,3 +68,12 @@ def test_host_side_argument_checks():
     with pytest.raises(zo_amd.ZoError):
         zo_amd.zo_kernel_lmhead_ce_noalloc(4096, 4096, 4096, 4096, 4096, zo_amd.ZO_BF16, 8, 60, 512)      # d not a multiple of 8
     assert zo_amd.zo_free(None) is None
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU is the whole target: `bench.py --gpus N` with N > 1 says so and exits before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "--gpus 1" in r.stderr and r.stdout.strip() == ""
