@@ -253,8 +253,11 @@ int zo_kernel_axpy_z(const void *src, void *dst, int dtype, uint64_t n, uint64_t
 int zo_kernel_axpy_z_sr(const void *src, void *dst, int dtype, uint64_t n, uint64_t seed,
                         uint32_t tensor_id, float scale, const float *dev_scale, void *stream);
 
-/* W+ = rn(theta + eps z), W- = rn(theta - eps z) for a [rows, cols] row-major tensor, written
- * transposed ([cols, rows], the layout the GEMMs read) when `transpose` is non-zero. */
+/* W+ = rn(theta + eps z), W- = rn(theta - eps z) (PertP workflow, Step 2; Alg. 1 PerturbParameters out of place)
+ * for a [rows, cols] row-major tensor, z of element i as everywhere: drawn at the element's index in theta.  Written
+ * in the same layout, or transposed ([cols, rows]) when `transpose` is non-zero (needs cols % 4 == 0): for a caller
+ * that keeps a matrix [in, out] and wants the [out, in] the GEMMs read.  The model's own tensors are [out, in]
+ * already and are staged with transpose = 0.  All three buffers: device, 16-byte aligned, not overlapping. */
 int zo_kernel_stage_pm(const void *theta, void *w_plus, void *w_minus, int dtype, int rows, int cols,
                        int transpose, uint64_t seed, uint32_t tensor_id, float eps, void *stream);
 
